@@ -1,0 +1,122 @@
+/*
+ * fsa.h -- C ABI of the MI355X (gfx950) fused neighbor-sampling + mean-aggregation library.
+ *
+ * The operations are those of arXiv 2511.13645 ("FuseSampleAgg"):
+ *   Sec. 3.2  for each seed v, draw up to k neighbors uniformly without replacement from its
+ *             CSR row and emit  h_nei(v) = (1/t) sum_{u in U(v)} X[u],  t = min(k, |N(v)|),
+ *             in one pass, with no sampled-subgraph ("block") tensor and no gathered-feature
+ *             tensor; for fanouts (k1,k2) emit the nested mean
+ *             X^_r = mean_{u in U1(r)} ( mean_{w in W(u)} X[w] ), skipping empty neighborhoods;
+ *   Sec. 3.3  Prop. 1 (fixed IDs give the plain mean of the named rows), seed-controlled
+ *             repeatable sampling, and saved-index replay so that backward reaches the same
+ *             neighborhoods;
+ *   Sec. 4    contiguous CSR (rowptr, col) and a contiguous row-major feature table.
+ *
+ * What the paper leaves open is fixed here, identically for every caller:
+ *   - the sampler is Floyd's k-of-n selection driven by Philox4x32-10; Floyd step i of row
+ *     `node` at hop h (0 = the seed's own row, 1 = a hop-1 node's row) uses word 0 of
+ *     Philox(counter = (node, h, i, 0), key = (seed & 0xffffffff, seed >> 32)), mapped to
+ *     [0, n) by (word * n) >> 32;  rows with deg <= k are taken whole in CSR order;
+ *   - sampling is over edge slots, so a multigraph row may emit the same ID twice; each
+ *     occurrence counts once in the sum and in the divisor;
+ *   - emitted IDs are in Floyd step order, unused slots hold -1, and ids2[b,j,:] is all -1
+ *     when ids1[b,j] is -1;
+ *   - in the 2-hop mean a hop-1 node with an empty row leaves both the sum and the divisor;
+ *     a seed with nothing to average gets a zero row (never NaN);
+ *   - sums are accumulated in fp32 in a fixed order; outputs have the feature type (bf16
+ *     outputs are rounded to nearest even from the fp32 result).
+ * Because every draw is keyed by (seed, node, hop, step) the sampled IDs do not depend on
+ * batch size, batch order, launch shape or how seeds are split over devices.
+ *
+ * Conventions for every entry point
+ *   - All array arguments are DEVICE pointers on the current HIP device unless marked HOST.
+ *     The caller owns every buffer; the library allocates nothing and keeps no state.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and return without synchronising.  Outputs are valid once the stream has drained.
+ *   - Return value: FSA_OK or a negative fsa_status.  Arguments are validated on the host
+ *     before anything is launched; on error nothing is launched and no output is written.
+ *     B == 0 returns FSA_OK without a launch (batch-sized arrays may then be NULL).
+ *   - Node IDs in `seeds`, `indices`, `ids1`, `ids2` must lie in [0, num_nodes) (or be
+ *     negative padding in ids1/ids2); this is not checked on the device.  Rows must be
+ *     shorter than 2^31 entries.
+ */
+#ifndef FSA_H
+#define FSA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FSA_F32 = 0, FSA_BF16 = 1 } fsa_dtype;   /* feature / output element type */
+typedef enum { FSA_I32 = 0, FSA_I64 = 1 } fsa_itype;    /* indptr element type           */
+
+typedef enum {
+    FSA_OK = 0,
+    FSA_ERR_NULL = -1,    /* a required pointer is NULL                                   */
+    FSA_ERR_ARG = -2,     /* a size, fanout or hop count is out of range                  */
+    FSA_ERR_DTYPE = -3,   /* unknown fsa_dtype / fsa_itype                                */
+    FSA_ERR_ALIGN = -4,   /* a pointer is not aligned to its element size                 */
+    FSA_ERR_HIP = -5      /* the HIP runtime refused the launch                           */
+} fsa_status;
+
+enum { FSA_KMAX = 64 };   /* largest fanout per hop (one wavefront lane per Floyd step)   */
+
+/*
+ * Fused sample + mean, forward (Sec. 3.2; kernel mapping of Sec. 4 re-derived for 64-wide
+ * wavefronts).
+ *   indptr      [num_nodes+1]  int32 or int64 per indptr_type
+ *   indices     [E]            int32 neighbor IDs
+ *   x           [num_nodes,D]  row-major, contiguous, fsa_dtype x_dtype
+ *   seeds       [B]            int32
+ *   fanouts     HOST array of num_hops entries (k1[,k2]); num_hops in {1,2}; 1 <= k <= FSA_KMAX
+ *   seed        sampler seed
+ *   out         [B,D]      x_dtype   1-hop: h_nei(seed);  2-hop: nested mean         (required)
+ *   out_h1      [B,k1,D]   x_dtype   2-hop: inner mean of every hop-1 slot, zero row for an
+ *                                    empty slot; may be NULL; must be NULL for 1-hop
+ *   out_ids1    [B,k1]     int32     sampled hop-1 IDs, -1 padded; may be NULL (no emit)
+ *   out_ids2    [B,k1,k2]  int32     sampled hop-2 IDs, -1 padded; may be NULL; NULL for 1-hop
+ * One kernel launch.  Deterministic and bit-reproducible for fixed arguments.
+ */
+int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                        int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                        const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                        uint64_t seed, void* out, void* out_h1,
+                        int32_t* out_ids1, int32_t* out_ids2, void* stream);
+
+/*
+ * Replay forward from saved IDs (Sec. 3.3, Prop. 1 and "Reproducibility").
+ *   ids1 [B,k1], ids2 [B,k1,k2] int32; ids2 == NULL selects 1-hop (k2 ignored).
+ * A negative entry is an empty slot and may appear anywhere.  In 2-hop, slot j takes part
+ * only if ids1[b,j] >= 0 and ids2[b,j,:] holds at least one non-negative ID.
+ * Given the arrays emitted by fsa_sample_mean_fwd and the same x, `out` and `out_h1` are
+ * bitwise identical to that call's (same summation order).
+ */
+int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                        const int32_t* ids1, const int32_t* ids2,
+                        int64_t B, int32_t k1, int32_t k2,
+                        void* out, void* out_h1, void* stream);
+
+/*
+ * Backward of the mean with respect to the feature table, replaying saved IDs (Sec. 3.3
+ * "Reproducibility": gradients correspond to the same sampled neighborhoods).
+ *   1-hop:  grad_x[ids1[b,i],:] += grad_out[b,:] / cnt_b
+ *   2-hop:  grad_x[ids2[b,j,i],:] += (grad_out[b,:] / c1_b + grad_h1[b,j,:]) / c2_bj
+ *           over slots j that take part (see replay), c1_b = number of such slots.
+ *   grad_out [B,D] fp32;  grad_h1 [B,k1,D] fp32, may be NULL;  grad_x [num_nodes,D] fp32.
+ * grad_x is ACCUMULATED INTO with fp32 atomics (the caller zeroes it or chains calls);
+ * the order of additions, and therefore the last bits, vary from run to run.
+ */
+int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
+                 const int32_t* ids1, const int32_t* ids2,
+                 int64_t B, int32_t k1, int32_t k2, int64_t D,
+                 float* grad_x, int64_t num_nodes, void* stream);
+
+/* Static, never-freed description of a status code. */
+const char* fsa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FSA_H */

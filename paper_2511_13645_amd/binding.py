@@ -1,0 +1,182 @@
+"""Thin ctypes binding of the C-ABI HIP library (include/fsa.h), same names as the C entry
+points.  Argument marshalling only: every step of the path runs inside the library's
+kernels.  PyTorch is used for device memory and the current stream, nothing else.
+
+The library must have been built (``python -m paper_2511_13645_amd.build`` or
+``__graft_entry__.build()``); there is no CPU fallback -- a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfsa_hip.so")
+
+FSA_F32, FSA_BF16 = 0, 1
+FSA_I32, FSA_I64 = 0, 1
+FSA_OK = 0
+FSA_KMAX = 64
+
+EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_status_string")
+
+_lib: Optional[ctypes.CDLL] = None
+
+
+class FsaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_string(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; fail loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("HIP library missing: %s (build it with __graft_entry__.build())" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, u64, ci = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint64, ctypes.c_int
+        L.fsa_sample_mean_fwd.argtypes = [vp, ci, vp, i64, vp, ci, i64, vp, i64, vp, ci, u64,
+                                          vp, vp, vp, vp, vp]
+        L.fsa_sample_mean_fwd.restype = ci
+        L.fsa_mean_replay_fwd.argtypes = [vp, ci, i64, i64, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.fsa_mean_replay_fwd.restype = ci
+        L.fsa_mean_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
+        L.fsa_mean_bwd.restype = ci
+        L.fsa_status_string.argtypes = [ci]
+        L.fsa_status_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().fsa_status_string(int(status)).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _x_dtype(x: torch.Tensor) -> int:
+    if x.dtype == torch.float32:
+        return FSA_F32
+    if x.dtype == torch.bfloat16:
+        return FSA_BF16
+    raise TypeError("features must be float32 or bfloat16, got %s" % x.dtype)
+
+
+def _indptr_type(indptr: torch.Tensor) -> int:
+    if indptr.dtype == torch.int32:
+        return FSA_I32
+    if indptr.dtype == torch.int64:
+        return FSA_I64
+    raise TypeError("indptr must be int32 or int64, got %s" % indptr.dtype)
+
+
+def _need(t: torch.Tensor, name: str, dtype=None) -> None:
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+
+
+def _stream(stream: Optional[torch.cuda.Stream]) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def fsa_sample_mean_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.Tensor,
+                        seeds: torch.Tensor, fanouts: Sequence[int], seed: int, *,
+                        out: Optional[torch.Tensor] = None, out_h1: Optional[torch.Tensor] = None,
+                        out_ids1: Optional[torch.Tensor] = None, out_ids2: Optional[torch.Tensor] = None,
+                        emit_h1: bool = True, emit_ids: bool = True,
+                        stream: Optional[torch.cuda.Stream] = None
+                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor], Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """Fused sample + mean forward.  Output tensors are allocated here (torch) unless given.
+    Returns (out, out_h1, ids1, ids2); entries not asked for are None."""
+    _need(indptr, "indptr"); _need(indices, "indices", torch.int32); _need(x, "x")
+    _need(seeds, "seeds", torch.int32)
+    fan = [int(k) for k in fanouts]
+    hops = len(fan)
+    B, (N, D) = seeds.shape[0], x.shape
+    if indptr.shape[0] != N + 1:
+        raise ValueError("indptr must have num_nodes+1 entries")
+    dev = x.device
+    k1 = fan[0] if hops >= 1 else 0
+    k2 = fan[1] if hops >= 2 else 0
+    if out is None:
+        out = torch.empty((B, D), dtype=x.dtype, device=dev)
+    if hops == 2 and emit_h1 and out_h1 is None:
+        out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev)
+    if emit_ids and out_ids1 is None:
+        out_ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev)
+    if emit_ids and hops == 2 and out_ids2 is None:
+        out_ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev)
+    for t, n in ((out, "out"), (out_h1, "out_h1"), (out_ids1, "out_ids1"), (out_ids2, "out_ids2")):
+        if t is not None:
+            _need(t, n)
+    fan_host = (ctypes.c_int32 * max(1, hops))(*fan)
+    rc = lib().fsa_sample_mean_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N,
+                                   _ptr(x), _x_dtype(x), D, _ptr(seeds), B,
+                                   ctypes.cast(fan_host, ctypes.c_void_p), hops, seed & (2**64 - 1),
+                                   _ptr(out), _ptr(out_h1), _ptr(out_ids1), _ptr(out_ids2), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_sample_mean_fwd")
+    return out, out_h1, out_ids1, out_ids2
+
+
+def fsa_mean_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torch.Tensor] = None, *,
+                        out: Optional[torch.Tensor] = None, out_h1: Optional[torch.Tensor] = None,
+                        emit_h1: bool = True, stream: Optional[torch.cuda.Stream] = None
+                        ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """Mean over saved IDs (no sampling).  Returns (out, out_h1)."""
+    _need(x, "x"); _need(ids1, "ids1", torch.int32)
+    B, k1 = ids1.shape
+    N, D = x.shape
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32)
+        if ids2.shape[0] != B or ids2.shape[1] != k1:
+            raise ValueError("ids2 must be [B,k1,k2]")
+        k2 = ids2.shape[2]
+    if out is None:
+        out = torch.empty((B, D), dtype=x.dtype, device=x.device)
+    if ids2 is not None and emit_h1 and out_h1 is None:
+        out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=x.device)
+    rc = lib().fsa_mean_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), B, k1, k2,
+                                   _ptr(out), _ptr(out_h1), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean_replay_fwd")
+    return out, out_h1
+
+
+def fsa_mean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torch.Tensor] = None,
+                 grad_h1: Optional[torch.Tensor] = None, *, grad_x: torch.Tensor,
+                 stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Scatter-add the mean's gradient into grad_x [N,D] fp32 (accumulated, not zeroed)."""
+    _need(grad_out, "grad_out", torch.float32); _need(ids1, "ids1", torch.int32)
+    _need(grad_x, "grad_x", torch.float32)
+    B, k1 = ids1.shape
+    D = grad_out.shape[1]
+    N = grad_x.shape[0]
+    if grad_x.shape[1] != D or grad_out.shape[0] != B:
+        raise ValueError("shape mismatch between grad_out, ids1 and grad_x")
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32)
+        k2 = ids2.shape[2]
+    if grad_h1 is not None:
+        _need(grad_h1, "grad_h1", torch.float32)
+        if tuple(grad_h1.shape) != (B, k1, D):
+            raise ValueError("grad_h1 must be [B,k1,D]")
+    rc = lib().fsa_mean_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(ids1), _ptr(ids2), B, k1, k2, D,
+                            _ptr(grad_x), N, _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean_bwd")
+    return grad_x

@@ -1,0 +1,48 @@
+"""Builds the HIP library (gfx950) in-tree: ``paper_2511_13645_amd/libfsa_hip.so``."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libfsa_hip.so")
+SOURCES = ["fsa_api.hip", "fsa_fwd.hip", "fsa_bwd.hip"]
+HEADERS = ["fsa_device.hip.h", "fsa_internal.h", os.path.join("..", "..", "include", "fsa.h")]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-munsafe-fp-atomics",
+    # keep hipcc from forming packed-fp32 instructions out of scalar float code
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-function",
+]
+
+
+def hipcc() -> str:
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.sep not in cand or os.path.exists(cand)):
+            return cand
+    return "hipcc"
+
+
+def build_hip(extra_flags=(), verbose: bool = False) -> str:
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True, cwd=CSRC)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    newest = max(os.path.getmtime(os.path.join(CSRC, f)) for f in SOURCES + HEADERS)
+    return os.path.getmtime(LIB) < newest
+
+
+if __name__ == "__main__":
+    print(build_hip(sys.argv[1:], verbose=True))

@@ -1,0 +1,132 @@
+// The C ABI declared in include/fsa.h: host-side validation, row geometry, dispatch.
+// Nothing here allocates, synchronises or keeps state.
+#include "../../include/fsa.h"
+#include "fsa_internal.h"
+
+namespace {
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Largest load width (bytes) that divides the row size and every pointer that is indexed by
+// whole rows, then the sub-group shape that covers a row.
+fsa::RowGeom row_geometry(int64_t D, int elem_bytes, const void* const* row_ptrs, int n_ptrs) {
+    const int64_t row_bytes = D * elem_bytes;
+    int vb = 16;
+    for (; vb > elem_bytes; vb >>= 1) {
+        bool ok = (row_bytes % vb) == 0;
+        for (int i = 0; ok && i < n_ptrs; ++i)
+            if (row_ptrs[i]) ok = aligned(row_ptrs[i], (uintptr_t)vb);
+        if (ok) break;
+    }
+    fsa::RowGeom g;
+    g.vec_bytes = vb;
+    g.chunks = (int)(row_bytes / vb);
+    int sub = 1;
+    while (sub < g.chunks && sub < 64) sub <<= 1;
+    g.sub = sub;
+    g.tiles = (g.chunks + sub - 1) / sub;
+    return g;
+}
+
+int check_common(int x_dtype, int64_t D, int64_t num_nodes, int64_t B) {
+    if (x_dtype != FSA_F32 && x_dtype != FSA_BF16) return FSA_ERR_DTYPE;
+    if (D <= 0 || D > (int64_t)1 << 24 || num_nodes <= 0 || num_nodes > (int64_t)INT32_MAX) return FSA_ERR_ARG;
+    if (B < 0 || B > (int64_t)INT32_MAX) return FSA_ERR_ARG;
+    return FSA_OK;
+}
+
+bool fanout_ok(int32_t k) { return k >= 1 && k <= FSA_KMAX; }
+
+}  // namespace
+
+extern "C" {
+
+int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                        int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                        const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                        uint64_t seed, void* out, void* out_h1,
+                        int32_t* out_ids1, int32_t* out_ids2, void* stream) {
+    if (!indptr || !indices || !x || !fanouts) return FSA_ERR_NULL;
+    if (B != 0 && (!seeds || !out)) return FSA_ERR_NULL;   // batch-sized arrays may be NULL when empty
+    if (indptr_type != FSA_I32 && indptr_type != FSA_I64) return FSA_ERR_DTYPE;
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    if (num_hops != 1 && num_hops != 2) return FSA_ERR_ARG;
+    const int32_t k1 = fanouts[0];
+    const int32_t k2 = num_hops == 2 ? fanouts[1] : 0;
+    if (!fanout_ok(k1) || (num_hops == 2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (num_hops == 1 && (out_h1 || out_ids2)) return FSA_ERR_ARG;
+    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    if (!aligned(indptr, indptr_type == FSA_I64 ? 8 : 4) || !aligned(indices, 4) || !aligned(seeds, 4) ||
+        !aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) ||
+        !aligned(out_ids1, 4) || !aligned(out_ids2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    const void* rows[3] = {x, out, out_h1};
+    fsa::FwdArgs a{};
+    a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
+    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.seeds = seeds; a.B = B; a.k1 = k1; a.k2 = k2; a.hops = num_hops; a.seed = seed;
+    a.ids1 = nullptr; a.ids2 = nullptr;
+    a.out = out; a.out_h1 = out_h1; a.out_ids1 = out_ids1; a.out_ids2 = out_ids2;
+    a.geom = row_geometry(D, eb, rows, 3);
+    return fsa::launch_forward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                        const int32_t* ids1, const int32_t* ids2,
+                        int64_t B, int32_t k1, int32_t k2,
+                        void* out, void* out_h1, void* stream) {
+    if (!x) return FSA_ERR_NULL;
+    if (B != 0 && (!ids1 || !out)) return FSA_ERR_NULL;    // batch-sized arrays may be NULL when empty
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && out_h1) return FSA_ERR_ARG;
+    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(ids1, 4) || !aligned(ids2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    const void* rows[3] = {x, out, out_h1};
+    fsa::FwdArgs a{};
+    a.indptr = nullptr; a.indices = nullptr; a.seeds = nullptr;
+    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.hops = ids2 ? 2 : 1; a.seed = 0;
+    a.ids1 = ids1; a.ids2 = ids2;
+    a.out = out; a.out_h1 = out_h1; a.out_ids1 = nullptr; a.out_ids2 = nullptr;
+    a.geom = row_geometry(D, eb, rows, 3);
+    return fsa::launch_forward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
+                 const int32_t* ids1, const int32_t* ids2,
+                 int64_t B, int32_t k1, int32_t k2, int64_t D,
+                 float* grad_x, int64_t num_nodes, void* stream) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1)) return FSA_ERR_NULL;   // batch-sized arrays may be NULL when empty
+    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && grad_h1) return FSA_ERR_ARG;
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    fsa::BwdArgs a{};
+    a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
+    return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+const char* fsa_status_string(int status) {
+    switch (status) {
+        case FSA_OK:        return "ok";
+        case FSA_ERR_NULL:  return "a required pointer is NULL";
+        case FSA_ERR_ARG:   return "a size, fanout or hop count is out of range";
+        case FSA_ERR_DTYPE: return "unknown element type";
+        case FSA_ERR_ALIGN: return "a pointer is not aligned to its element size";
+        case FSA_ERR_HIP:   return "the HIP runtime refused the launch";
+        default:            return "unknown status";
+    }
+}
+
+}  // extern "C"

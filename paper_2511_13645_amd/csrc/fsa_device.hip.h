@@ -1,0 +1,183 @@
+// Device-side building blocks shared by the forward, replay and backward kernels (gfx950,
+// 64-lane wavefronts): the counter-based sampler and the 16/8/4/2-byte feature-row chunks.
+// HIP path only; the CPU oracle has its own, separate implementation.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fsa {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  Only output word 0 is consumed: one generator call
+// per Floyd step, so a draw is a pure function of (seed, node, hop, step).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1, uint32_t c2,
+                                                        uint32_t c3, uint32_t k0, uint32_t k1) {
+    constexpr uint32_t kMulA = 0xD2511F53u, kMulB = 0xCD9E8D57u;
+    constexpr uint32_t kWeylA = 0x9E3779B9u, kWeylB = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        if (r) { k0 += kWeylA; k1 += kWeylB; }
+        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
+        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+        const uint32_t n0 = hiB ^ c1 ^ k0;
+        const uint32_t n2 = hiA ^ c3 ^ k1;
+        c0 = n0; c1 = loB; c2 = n2; c3 = loA;
+    }
+    return c0;
+}
+
+__device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane) - 1ull; }
+
+// ---------------------------------------------------------------------------------------
+// Floyd's k-of-deg selection, one lane per step, for several rows at once.
+//
+// The wave is cut into segments of k consecutive lanes starting at seg_base; lane
+// seg_base+li runs step li of its segment's row.  All 64 lanes must call this together
+// (it shuffles and ballots); lanes without a row pass active=false.
+//
+// Sequential Floyd inserts t_i unless it is already chosen, else J_i = deg-k+i.  Whatever
+// happens at step m, t_m is in the set afterwards, and J_m is in it exactly when step m
+// collided; J_i exceeds everything chosen before step i.  So the set before step i is
+// {t_m : m<i} U {J_m : m<i, step m collided}, and
+//     collided_i = (exists m<i: t_m == t_i)  or  (t_i == J_m for an m<i with collided_m).
+// The first term is a segment-wide compare; the second is resolved in k ballot rounds, step
+// i being final in round i because it only looks at earlier steps.
+//
+// Returns this lane's position inside the row (0-based), or -1 for an unused slot.
+// deg <= k keeps the whole row in CSR order (Sec. 3.2: t = min(k, |N(v)|)).
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, uint32_t hop,
+                                                  int k, int li, int seg_base, int64_t deg,
+                                                  bool active, int lane) {
+    const bool floyd = active && deg > (int64_t)k;
+    uint32_t t = 0u;
+    const uint32_t base = floyd ? (uint32_t)(deg - k) : 0u;          // J_i = base + li
+    if (floyd) {
+        const uint32_t r = philox4x32_10_word0(node, hop, (uint32_t)li, 0u,
+                                               (uint32_t)seed, (uint32_t)(seed >> 32));
+        t = __umulhi(r, base + (uint32_t)li + 1u);                   // uniform in [0, J_i]
+    }
+    bool collided = false;
+    if (__any(floyd)) {                                              // wave-uniform
+        bool dup_earlier = false;
+        for (int m = 0; m < k; ++m) {
+            const uint32_t tm = (uint32_t)__shfl((int)t, seg_base + m);
+            dup_earlier = dup_earlier || (m < li && tm == t);
+        }
+        const bool hits_J = floyd && t >= base && (t - base) < (uint32_t)li;
+        const int dep_lane = seg_base + (int)(t - base);
+        uint64_t done = 0ull;                                        // collided flags, final per round
+        for (int i = 0; i < k; ++i) {
+            const bool c = floyd && (dup_earlier || (hits_J && ((done >> (dep_lane & 63)) & 1ull)));
+            done |= __ballot(c && li == i);
+        }
+        collided = (done >> lane) & 1ull;
+    }
+    if (floyd) return collided ? (int64_t)(base + (uint32_t)li) : (int64_t)t;
+    return (active && (int64_t)li < deg) ? (int64_t)li : -1;
+}
+
+template <typename IT>
+__device__ __forceinline__ int64_t load_indptr(const void* indptr, int64_t i) {
+    return (int64_t) static_cast<const IT*>(indptr)[i];
+}
+
+// ---------------------------------------------------------------------------------------
+// A chunk is what one lane loads from a feature row in one instruction: VB bytes = VE
+// elements, widened to fp32 accumulators.
+// ---------------------------------------------------------------------------------------
+struct f32_t { float v; };
+struct bf16_t { uint16_t v; };
+
+template <int VB> struct RawOf;
+template <> struct RawOf<16> { using type = uint4; };
+template <> struct RawOf<8>  { using type = uint2; };
+template <> struct RawOf<4>  { using type = uint32_t; };
+template <> struct RawOf<2>  { using type = uint16_t; };
+
+__device__ __forceinline__ float bits_f32(uint32_t u) { return __uint_as_float(u); }
+
+// fp32 -> bfloat16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <typename XT, int VB> struct Chunk;
+
+template <int VB> struct Chunk<f32_t, VB> {
+    static constexpr int VE = VB / 4;
+    using Raw = typename RawOf<VB>::type;
+    static __device__ __forceinline__ void add(float (&acc)[VE], const Raw& r) {
+        if constexpr (VB == 16) { acc[0] += bits_f32(r.x); acc[1] += bits_f32(r.y); acc[2] += bits_f32(r.z); acc[3] += bits_f32(r.w); }
+        else if constexpr (VB == 8) { acc[0] += bits_f32(r.x); acc[1] += bits_f32(r.y); }
+        else { acc[0] += bits_f32(r); }
+    }
+    static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {
+        Raw r;
+        if constexpr (VB == 16) { r.x = __float_as_uint(v[0]); r.y = __float_as_uint(v[1]); r.z = __float_as_uint(v[2]); r.w = __float_as_uint(v[3]); }
+        else if constexpr (VB == 8) { r.x = __float_as_uint(v[0]); r.y = __float_as_uint(v[1]); }
+        else { r = __float_as_uint(v[0]); }
+        return r;
+    }
+};
+
+template <int VB> struct Chunk<bf16_t, VB> {
+    static constexpr int VE = VB / 2;
+    using Raw = typename RawOf<VB>::type;
+    static __device__ __forceinline__ void add2(float& lo, float& hi, uint32_t w) {
+        lo += bits_f32(w << 16);
+        hi += bits_f32(w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void add(float (&acc)[VE], const Raw& r) {
+        if constexpr (VB == 16) { add2(acc[0], acc[1], r.x); add2(acc[2], acc[3], r.y); add2(acc[4], acc[5], r.z); add2(acc[6], acc[7], r.w); }
+        else if constexpr (VB == 8) { add2(acc[0], acc[1], r.x); add2(acc[2], acc[3], r.y); }
+        else if constexpr (VB == 4) { add2(acc[0], acc[1], r); }
+        else { acc[0] += bits_f32(((uint32_t)r) << 16); }
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    }
+    static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {
+        Raw r;
+        if constexpr (VB == 16) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); r.z = pack2(v[4], v[5]); r.w = pack2(v[6], v[7]); }
+        else if constexpr (VB == 8) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); }
+        else if constexpr (VB == 4) { r = pack2(v[0], v[1]); }
+        else { r = (uint16_t)f32_to_bf16_bits(v[0]); }
+        return r;
+    }
+};
+
+// Sum the chunk at byte offset `chunk_off` of rows ids[first], ids[first+stride], ... (index
+// below count) into acc, in that order.  Up to UNROLL row loads are issued before the first
+// add so that their latencies overlap.  `ids` lives in LDS.
+template <typename XT, int VB, int UNROLL>
+__device__ __forceinline__ void sum_row_chunks(const char* __restrict__ x, int64_t row_bytes,
+                                               int64_t chunk_off, const int* ids, int first,
+                                               int count, int stride,
+                                               float (&acc)[Chunk<XT, VB>::VE]) {
+    using C = Chunk<XT, VB>;
+    using Raw = typename C::Raw;
+    for (int i0 = first; i0 < count; i0 += stride * UNROLL) {
+        Raw r[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int i = i0 + u * stride;
+            if (i < count)
+                r[u] = *reinterpret_cast<const Raw*>(x + (int64_t)ids[i] * row_bytes + chunk_off);
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int i = i0 + u * stride;
+            if (i < count) C::add(acc, r[u]);
+        }
+    }
+}
+
+}  // namespace fsa

@@ -1,0 +1,34 @@
+// Host-side launch interface between the C ABI (fsa_api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fsa {
+
+// How a feature row is cut into per-lane chunks and how lanes are grouped over rows.
+struct RowGeom {
+    int vec_bytes;     // 16, 8, 4 or 2: bytes one lane loads per instruction
+    int chunks;        // chunks per row = D * elem_bytes / vec_bytes
+    int sub;           // lanes that cover one row together: min(64, pow2 >= chunks)
+    int tiles;         // passes of `sub` lanes needed to cover a row
+};
+
+struct FwdArgs {
+    const void* indptr; int indptr_is64; const int32_t* indices;
+    const void* x; int x_is_bf16; int64_t D;
+    const int32_t* seeds; int64_t B; int k1; int k2; int hops; uint64_t seed;
+    const int32_t* ids1; const int32_t* ids2;   // replay inputs (indptr == nullptr selects replay)
+    void* out; void* out_h1; int32_t* out_ids1; int32_t* out_ids2;
+    RowGeom geom;
+};
+
+struct BwdArgs {
+    const float* grad_out; const float* grad_h1; const int32_t* ids1; const int32_t* ids2;
+    int64_t B; int k1; int k2; int64_t D; float* grad_x;
+};
+
+hipError_t launch_forward(const FwdArgs& a, hipStream_t stream);
+hipError_t launch_backward(const BwdArgs& a, hipStream_t stream);
+
+}  // namespace fsa

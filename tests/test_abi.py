@@ -1,0 +1,103 @@
+"""The C-ABI library: it loads, exports every symbol the header declares, and its host-side
+argument validation answers with the documented status codes without launching anything
+(no GPU needed: validation happens before the first HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fsa.h")
+
+
+@pytest.fixture(scope="module")
+def fsa():
+    from paper_2511_13645_amd import binding, build
+    if build.is_stale():
+        build.build_hip()
+    return binding
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fsa_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(fsa):
+    names = _declared()
+    assert set(names) == set(fsa.EXPORTS)
+    L = fsa.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings(fsa):
+    seen = {fsa.status_string(s) for s in range(0, -6, -1)}
+    assert len(seen) == 6 and "ok" in seen
+    assert fsa.status_string(-99) == "unknown status"
+
+
+FAKE = 0x10000   # non-null, 16-byte aligned; never dereferenced on an error path
+
+
+def _fwd(fsa, **kw):
+    a = dict(indptr=FAKE, itype=0, indices=FAKE, n=100, x=FAKE, xt=0, D=16, seeds=FAKE, B=8,
+             fan=[5, 3], hops=2, seed=1, out=FAKE, out_h1=FAKE, ids1=FAKE, ids2=FAKE)
+    a.update(kw)
+    fan = (ctypes.c_int32 * 2)(*((a["fan"] + [0])[:2])) if a["fan"] is not None else None
+    return fsa.lib().fsa_sample_mean_fwd(a["indptr"], a["itype"], a["indices"], a["n"], a["x"], a["xt"],
+                                         a["D"], a["seeds"], a["B"],
+                                         ctypes.cast(fan, ctypes.c_void_p) if fan is not None else None,
+                                         a["hops"], a["seed"], a["out"], a["out_h1"], a["ids1"], a["ids2"], None)
+
+
+def test_forward_rejects_bad_arguments(fsa):
+    assert _fwd(fsa, indptr=None) == -1
+    assert _fwd(fsa, indices=None) == -1
+    assert _fwd(fsa, x=None) == -1
+    assert _fwd(fsa, seeds=None) == -1
+    assert _fwd(fsa, out=None) == -1
+    assert _fwd(fsa, fan=None) == -1
+    assert _fwd(fsa, hops=0) == -2 and _fwd(fsa, hops=3) == -2
+    assert _fwd(fsa, fan=[0, 3]) == -2 and _fwd(fsa, fan=[65, 3]) == -2 and _fwd(fsa, fan=[5, 65]) == -2
+    assert _fwd(fsa, fan=[5, -1]) == -2
+    assert _fwd(fsa, D=0) == -2 and _fwd(fsa, B=-1) == -2 and _fwd(fsa, n=0) == -2
+    assert _fwd(fsa, xt=2) == -3 and _fwd(fsa, itype=5) == -3
+    assert _fwd(fsa, x=FAKE + 2) == -4               # fp32 table on a 2-byte boundary
+    assert _fwd(fsa, x=FAKE + 1, xt=1) == -4         # bf16 table on an odd address
+    assert _fwd(fsa, indptr=FAKE + 4, itype=1) == -4
+    assert _fwd(fsa, ids1=FAKE + 2) == -4
+    # 1-hop takes no hop-2 outputs
+    assert _fwd(fsa, hops=1, fan=[5]) == -2
+    # B == 0: nothing to do, nothing launched
+    assert _fwd(fsa, B=0) == 0
+    assert _fwd(fsa, B=0, hops=1, fan=[64], out_h1=None, ids2=None, ids1=None) == 0
+
+
+def test_replay_and_backward_reject_bad_arguments(fsa):
+    L = fsa.lib()
+    rp = lambda **k: L.fsa_mean_replay_fwd(*[{**dict(x=FAKE, xt=0, D=8, n=10, ids1=FAKE, ids2=FAKE, B=4, k1=3,
+                                                   k2=2, out=FAKE, out_h1=FAKE, s=None), **k}[n]
+                                             for n in ("x", "xt", "D", "n", "ids1", "ids2", "B", "k1", "k2", "out", "out_h1", "s")])
+    assert rp(x=None) == -1 and rp(ids1=None) == -1 and rp(out=None) == -1
+    assert rp(k1=0) == -2 and rp(k1=65) == -2 and rp(k2=0) == -2
+    assert rp(ids2=None, out_h1=FAKE) == -2          # 1-hop has no per-slot output
+    assert rp(xt=7) == -3 and rp(out=FAKE + 1) == -4
+    assert rp(B=0) == 0 and rp(ids2=None, out_h1=None, k2=0, B=0) == 0
+    bw = lambda **k: L.fsa_mean_bwd(*[{**dict(go=FAKE, gh=FAKE, ids1=FAKE, ids2=FAKE, B=4, k1=3, k2=2, D=8,
+                                            gx=FAKE, n=10, s=None), **k}[n]
+                                      for n in ("go", "gh", "ids1", "ids2", "B", "k1", "k2", "D", "gx", "n", "s")])
+    assert bw(go=None) == -1 and bw(ids1=None) == -1 and bw(gx=None) == -1
+    assert bw(k1=0) == -2 and bw(k2=65) == -2 and bw(D=0) == -2 and bw(B=-3) == -2
+    assert bw(ids2=None, gh=FAKE) == -2
+    assert bw(gx=FAKE + 2) == -4
+    assert bw(B=0) == 0
+
+
+def test_binding_fails_loudly_without_library(fsa, monkeypatch):
+    monkeypatch.setattr(fsa, "_lib", None)
+    monkeypatch.setattr(fsa, "LIB_PATH", "/nonexistent/libfsa_hip.so")
+    with pytest.raises(RuntimeError, match="HIP library missing"):
+        fsa.lib()
