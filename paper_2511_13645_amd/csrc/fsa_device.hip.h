@@ -21,8 +21,9 @@ __device__ __forceinline__ uint32_t philox4x32_10_word0(uint32_t c0, uint32_t c1
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
         if (r) { k0 += kWeylA; k1 += kWeylB; }
-        const uint32_t hiA = __umulhi(kMulA, c0), loA = kMulA * c0;
-        const uint32_t hiB = __umulhi(kMulB, c2), loB = kMulB * c2;
+        const uint64_t pa = (uint64_t)kMulA * c0, pb = (uint64_t)kMulB * c2;   // one 32x32->64 multiply each
+        const uint32_t hiA = (uint32_t)(pa >> 32), loA = (uint32_t)pa;
+        const uint32_t hiB = (uint32_t)(pb >> 32), loB = (uint32_t)pb;
         const uint32_t n0 = hiB ^ c1 ^ k0;
         const uint32_t n2 = hiA ^ c3 ^ k1;
         c0 = n0; c1 = loB; c2 = n2; c3 = loA;
@@ -44,8 +45,8 @@ __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane
 // collided; J_i exceeds everything chosen before step i.  So the set before step i is
 // {t_m : m<i} U {J_m : m<i, step m collided}, and
 //     collided_i = (exists m<i: t_m == t_i)  or  (t_i == J_m for an m<i with collided_m).
-// The first term is a segment-wide compare; the second is resolved in k ballot rounds, step
-// i being final in round i because it only looks at earlier steps.
+// The first term is a segment-wide compare; the second is resolved by ballot rounds that
+// propagate collisions along the (acyclic, backward-pointing) J dependencies.
 //
 // Returns this lane's position inside the row (0-based), or -1 for an unused slot.
 // deg <= k keeps the whole row in CSR order (Sec. 3.2: t = min(k, |N(v)|)).
@@ -70,10 +71,14 @@ __device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, 
         }
         const bool hits_J = floyd && t >= base && (t - base) < (uint32_t)li;
         const int dep_lane = seg_base + (int)(t - base);
-        uint64_t done = 0ull;                                        // collided flags, final per round
-        for (int i = 0; i < k; ++i) {
-            const bool c = floyd && (dup_earlier || (hits_J && ((done >> (dep_lane & 63)) & 1ull)));
-            done |= __ballot(c && li == i);
+        // Least fixed point of  c_i = dup_i | (hits_J_i & c_dep(i)):  dependencies only point to
+        // earlier steps, so iterating from the dup flags converges to the sequential answer,
+        // usually in one or two rounds because chains of replaced values are rare.
+        uint64_t done = __ballot(floyd && dup_earlier);
+        for (;;) {
+            const uint64_t more = __ballot(hits_J && ((done >> (dep_lane & 63)) & 1ull));
+            if ((more & ~done) == 0ull) break;
+            done |= more;
         }
         collided = (done >> lane) & 1ull;
     }
@@ -101,13 +106,9 @@ template <> struct RawOf<2>  { using type = uint16_t; };
 
 __device__ __forceinline__ float bits_f32(uint32_t u) { return __uint_as_float(u); }
 
-// fp32 -> bfloat16 bits, round to nearest even (NaN stays NaN).
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// 1/n for a small positive count n: the hardware reciprocal is within 1 ulp, far inside the
+// 1e-5 relative budget of the means, and turns VE divisions per mean into VE multiplies.
+__device__ __forceinline__ float inv_count(int n) { return __builtin_amdgcn_rcpf((float)n); }
 
 template <typename XT, int VB> struct Chunk;
 
@@ -142,14 +143,21 @@ template <int VB> struct Chunk<bf16_t, VB> {
         else { acc[0] += bits_f32(((uint32_t)r) << 16); }
     }
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
-        return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+        // fptrunc to bfloat16 is round-to-nearest-even; gfx950 does a pair per instruction
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const f32x2 v = {lo, hi};
+        const bf16x2 b = __builtin_convertvector(v, bf16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &b, sizeof u);
+        return u;
     }
     static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {
         Raw r;
         if constexpr (VB == 16) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); r.z = pack2(v[4], v[5]); r.w = pack2(v[6], v[7]); }
         else if constexpr (VB == 8) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); }
         else if constexpr (VB == 4) { r = pack2(v[0], v[1]); }
-        else { r = (uint16_t)f32_to_bf16_bits(v[0]); }
+        else { r = (uint16_t)(pack2(v[0], 0.0f) & 0xffffu); }
         return r;
     }
 };

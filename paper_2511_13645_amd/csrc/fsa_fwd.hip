@@ -22,7 +22,13 @@
 #include <cstdlib>
 
 #ifndef FSA_UNROLL
-#define FSA_UNROLL 10
+#define FSA_UNROLL 8
+#endif
+#ifndef FSA_PASS_GROUP
+#define FSA_PASS_GROUP 4
+#endif
+#ifndef FSA_FWD2_MIN_WAVES_PER_EU
+#define FSA_FWD2_MIN_WAVES_PER_EU 1
 #endif
 
 namespace fsa {
@@ -35,8 +41,18 @@ struct FwdParams {
     int k1, k2, chunks, sub, sub_shift, indptr_is64;
 };
 
-__device__ __forceinline__ int64_t indptr_at(const FwdParams& p, int64_t i) {
-    return p.indptr_is64 ? load_indptr<int64_t>(p.indptr, i) : load_indptr<int32_t>(p.indptr, i);
+// Row start and length of node i: both indptr entries are requested before either is used.
+__device__ __forceinline__ void row_extent(const FwdParams& p, int64_t i, int64_t& start, int64_t& deg) {
+    int64_t lo, hi;
+    if (p.indptr_is64) {
+        const int64_t* q = static_cast<const int64_t*>(p.indptr) + i;
+        lo = q[0]; hi = q[1];
+    } else {
+        const int32_t* q = static_cast<const int32_t*>(p.indptr) + i;
+        lo = q[0]; hi = q[1];
+    }
+    start = lo;
+    deg = hi - lo;
 }
 
 // Hop-0 step shared by both kernels: lane i < k1 ends up with the i-th sampled (or saved)
@@ -47,8 +63,8 @@ __device__ __forceinline__ int hop0_id(const FwdParams& p, int64_t b, int lane) 
         return lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
     } else {
         const int64_t r = p.seeds[b];
-        const int64_t s = indptr_at(p, r);
-        const int64_t deg = indptr_at(p, r + 1) - s;
+        int64_t s, deg;
+        row_extent(p, r, s, deg);
         const int64_t pos = floyd_position(p.seed, (uint32_t)r, 0u, p.k1, lane, 0, deg,
                                            lane < p.k1, lane);
         return pos >= 0 ? p.indices[s + pos] : -1;
@@ -81,7 +97,7 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
     const int sg = lane >> p.sub_shift;         // sub-group index within the wave
     const int sl = lane & (sub - 1);
     const int nsg = kWave >> p.sub_shift;
-    const float inv_guard = cnt > 0 ? (float)cnt : 1.0f;
+    const float inv_cnt = inv_count(cnt > 0 ? cnt : 1);
     for (int c0 = 0; c0 < p.chunks; c0 += sub) {
         const int chunk = c0 + sl;
         const bool live = chunk < p.chunks;
@@ -97,7 +113,7 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
         }
         if (sg == 0 && live) {
 #pragma unroll
-            for (int e = 0; e < VE; ++e) acc[e] = acc[e] / inv_guard;
+            for (int e = 0; e < VE; ++e) acc[e] *= inv_cnt;
             *reinterpret_cast<typename C::Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(acc);
         }
     }
@@ -105,11 +121,27 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
 
 // ---------------------------------------------------------------------------------------
 // 2-hop: workgroup per root, waves own interleaved hop-1 slots
+//
+// A root costs a chain of dependent memory steps (seed -> indptr -> indices -> indptr ->
+// indices -> feature rows); at the paper's batch sizes the launch is about as long as that
+// chain, so the kernel is laid out to take each step ONCE per wave, for all of its slots:
+//   step 1-3  hop 0 (every wave redraws it; lanes j < k1 end with U[j]);
+//   step 4    lane q reads the indptr pair of owned slot q (all slots in one go);
+//   step 5    Floyd positions for (slot, step) pairs, 64/k2 slots per pass, with the
+//             `indices` loads of up to kPassGroup passes in flight together;
+//   step 6    the leaf IDs of all owned slots are laid out as one flat list per sub-group
+//             (slot ends flagged in bit 31), so that the row loads run kUnroll deep across
+//             slot boundaries instead of one slot at a time.
 // ---------------------------------------------------------------------------------------
+constexpr int kPassGroup = FSA_PASS_GROUP;
+
 template <typename XT, int VB, bool REPLAY>
-__global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(FSA_FWD2_MIN_WAVES_PER_EU)))
+void fwd2_kernel(const FwdParams p) {
     using C = Chunk<XT, VB>;
+    using Raw = typename C::Raw;
     constexpr int VE = C::VE;
+    constexpr int U = FSA_UNROLL;
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -117,93 +149,175 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
     const int64_t b = blockIdx.x;
     const int k1 = p.k1, k2 = p.k2;
 
-    // LDS: per wave [nq_max*k2] leaf IDs + [nq_max] counts; then [nw] live-slot counts;
-    // then [nw][sub*VE] floats for the cross-wave reduction.
+    // LDS per wave: flat list of row byte offsets (int2, slot end flagged in bit 63)
+    // [nq_max*k2], leaf IDs by slot [nq_max*k2], slot-end records [nq_max*k2], per-slot count
+    // and flat offset [nq_max] each; then [nw] live-slot counts and [nw][sub*VE] floats for
+    // the cross-wave reduction.
     const int nq_max = (k1 + nw - 1) / nw;
-    int* leaf = smem + wave * (nq_max * k2 + nq_max);
-    int* cnt2 = leaf + nq_max * k2;
-    int* live_slots = smem + nw * (nq_max * k2 + nq_max);
+    const int per_wave = 4 * nq_max * k2 + 2 * nq_max;            // even: int2 stays 8-byte aligned
+    int2* flat = reinterpret_cast<int2*>(smem + wave * per_wave);
+    int* leaf = smem + wave * per_wave + 2 * nq_max * k2;
+    int* flat_meta = leaf + nq_max * k2;
+    int* cnt2 = flat_meta + nq_max * k2;
+    int* offs = cnt2 + nq_max;
+    int* live_slots = smem + nw * per_wave;
     float* red = reinterpret_cast<float*>(live_slots + nw);
 
     // hop 0, redundantly in every wave: lane j holds U[j]
     const int u_mine = hop0_id<REPLAY>(p, b, lane);
     if (!REPLAY && wave == 0 && p.out_ids1 && lane < k1) p.out_ids1[b * k1 + lane] = u_mine;
 
-    // hop 1 for the slots this wave owns: j = wave + q*nw, q < nq
+    // owned slots: j = wave + q*nw, q < nq; lane q keeps slot q's node, row start and degree
     const int nq = wave < k1 ? (k1 - wave + nw - 1) / nw : 0;
-    const int spw = kWave / k2;                          // rows sampled at once
-    const int g = lane / k2;
-    const int li = lane - g * k2;
-    for (int q0 = 0; q0 < nq; q0 += spw) {               // wave-uniform trip count
-        const int q = q0 + g;
-        const bool valid = g < spw && q < nq;
-        const int j = wave + q * nw;
-        const int u = __shfl(u_mine, valid ? j : 0);
-        const bool active = valid && u >= 0;
-        const int seg_base = valid ? g * k2 : 0;
-        int id = -1;
-        int c2 = 0;
-        if constexpr (REPLAY) {
-            if (active) id = p.ids2[(b * k1 + j) * k2 + li];
-            const uint64_t seg = (k2 == 64 ? ~0ull : ((1ull << k2) - 1ull)) << seg_base;
-            const uint64_t have = __ballot(id >= 0) & seg;
-            c2 = __popcll(have);
-            if (id >= 0) leaf[q * k2 + __popcll(have & lanemask_lt(lane))] = id;
-        } else {
-            int64_t s = 0, deg = 0;
-            if (active) {
-                s = indptr_at(p, u);
-                deg = indptr_at(p, (int64_t)u + 1) - s;
-            }
-            const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, seg_base, deg,
-                                               active, lane);
-            if (pos >= 0) id = p.indices[s + pos];
-            c2 = active ? (int)(deg < (int64_t)k2 ? deg : (int64_t)k2) : 0;
-            if (valid) {
-                leaf[q * k2 + li] = id;                  // valid IDs are a prefix of the slot
-                if (p.out_ids2) p.out_ids2[(b * k1 + j) * k2 + li] = id;
-            }
-        }
-        if (valid && li == 0) cnt2[q] = c2;
-    }
-    __builtin_amdgcn_wave_barrier();
-    {
-        const int mine = lane < nq ? cnt2[lane] : 0;
-        const int n_live = __popcll(__ballot(mine > 0));
-        if (lane == 0) live_slots[wave] = n_live;
+    const int u_own = __shfl(u_mine, lane < nq ? wave + lane * nw : 0);
+    int64_t s_own = 0, deg_own = 0;
+    if constexpr (!REPLAY) {
+        if (lane < nq && u_own >= 0) row_extent(p, u_own, s_own, deg_own);
+        if (lane < nq) cnt2[lane] = (int)(deg_own < (int64_t)k2 ? deg_own : (int64_t)k2);
     }
 
-    // gather: one sub-group per owned slot
+    // hop 1: (slot, step) pairs in passes of spw slots; loads of a pass group overlap
+    const int spw = kWave / k2;
+    const int g = lane / k2;
+    const int li = lane - g * k2;
+    for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {          // wave-uniform trip count
+        int idv[kPassGroup];
+#pragma unroll
+        for (int t = 0; t < kPassGroup; ++t) {
+            idv[t] = -1;
+            if (q0 + t * spw < nq) {                               // wave-uniform
+                const int q = q0 + t * spw + g;
+                const bool valid = g < spw && q < nq;
+                const int src = valid ? q : 0;
+                const int u = __shfl(u_own, src);
+                const bool active = valid && u >= 0;
+                if constexpr (REPLAY) {
+                    if (active) idv[t] = p.ids2[(b * k1 + wave + q * nw) * k2 + li];
+                } else {
+                    const uint32_t s_lo = __shfl((uint32_t)s_own, src);
+                    const uint32_t s_hi = __shfl((uint32_t)((uint64_t)s_own >> 32), src);
+                    const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
+                    const int64_t deg = (int64_t)(uint32_t)__shfl((uint32_t)deg_own, src);
+                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
+                                                       deg, active, lane);
+                    if (pos >= 0) idv[t] = p.indices[s + pos];
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kPassGroup; ++t) {
+            if (q0 + t * spw < nq) {
+                const int q = q0 + t * spw + g;
+                const bool valid = g < spw && q < nq;
+                if constexpr (REPLAY) {
+                    const int seg_base = valid ? g * k2 : 0;
+                    const uint64_t seg = (k2 == 64 ? ~0ull : ((1ull << k2) - 1ull)) << seg_base;
+                    const uint64_t have = __ballot(valid && idv[t] >= 0) & seg;
+                    if (valid && idv[t] >= 0) leaf[q * k2 + __popcll(have & lanemask_lt(lane))] = idv[t];
+                    if (valid && li == 0) cnt2[q] = __popcll(have);
+                } else if (valid) {
+                    leaf[q * k2 + li] = idv[t];                    // valid IDs are a prefix of the slot
+                    if (p.out_ids2) p.out_ids2[(b * k1 + wave + q * nw) * k2 + li] = idv[t];
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // flat lists: slot q goes to sub-group q % nsg; lists are stored back to back
     const int sub = p.sub;
     const int sg = lane >> p.sub_shift;
     const int sl = lane & (sub - 1);
     const int nsg = kWave >> p.sub_shift;
+    int my_start = 0, my_len = 0;        // this lane's sub-group list
+    {
+        int off_q = 0;                   // where slot `lane` starts (lanes < nq)
+        const int mq = lane & (nsg - 1);
+        for (int t = 0; t < nq; ++t) {
+            const int c = cnt2[t];
+            const int m = t & (nsg - 1);
+            my_start += m < sg ? c : 0;
+            my_len += m == sg ? c : 0;
+            off_q += (m < mq || (m == mq && t < lane)) ? c : 0;
+        }
+        if (lane < nq) offs[lane] = off_q;
+        const int mine = lane < nq ? cnt2[lane] : 0;
+        const int n_live = __popcll(__ballot(mine > 0));
+        if (lane == 0) live_slots[wave] = n_live;
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int q0 = 0; q0 < nq; q0 += spw) {
+        const int q = q0 + g;
+        if (g < spw && q < nq) {
+            const int c = cnt2[q];
+            if (li < c) {
+                const int at = offs[q] + li;
+                const uint64_t row_off = (uint64_t)(uint32_t)leaf[q * k2 + li] * (uint64_t)p.row_bytes;
+                flat[at] = make_int2((int)(uint32_t)row_off,
+                                     (int)((uint32_t)(row_off >> 32) | (li == c - 1 ? 0x80000000u : 0u)));
+                if (li == c - 1) flat_meta[at] = (wave + q * nw) | (c << 8);
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    // gather
     for (int c0 = 0; c0 < p.chunks; c0 += sub) {
         const int chunk = c0 + sl;
         const bool live = chunk < p.chunks;
         const int64_t chunk_off = (int64_t)chunk * VB;
-        float root[VE];
+        float acc[VE], root[VE];
 #pragma unroll
-        for (int e = 0; e < VE; ++e) root[e] = 0.0f;
-        for (int q = sg; q < nq; q += nsg) {
-            const int c = cnt2[q];
-            float acc[VE];
+        for (int e = 0; e < VE; ++e) { acc[e] = 0.0f; root[e] = 0.0f; }
+        if (p.out_h1 && live) {                                    // empty slots get zero rows
+            for (int q = sg; q < nq; q += nsg)
+                if (cnt2[q] == 0)
+                    *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + wave + q * nw) * p.row_bytes + chunk_off) = C::pack(acc);
+        }
+        // Row loads carry no branch of their own: past the end of the list they re-read its
+        // last row (a cache hit) and lanes beyond the row width re-read chunk 0; the results
+        // are simply not accumulated.  This keeps kUnroll loads in flight per lane.
+        const int64_t load_off = live ? chunk_off : 0;
+        for (int i0 = 0; i0 < my_len; i0 += U) {
+            int2 ent[U];
+            Raw r[U];
 #pragma unroll
-            for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
-            if (live && c > 0) {
-                sum_row_chunks<XT, VB, FSA_UNROLL>(p.x, p.row_bytes, chunk_off, leaf + q * k2, 0, c, 1, acc);
-                const float fc = (float)c;
-#pragma unroll
-                for (int e = 0; e < VE; ++e) { acc[e] = acc[e] / fc; root[e] += acc[e]; }
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u < my_len ? i0 + u : my_len - 1;
+                ent[u] = flat[my_start + i];
+                const uint64_t row_off = ((uint64_t)((uint32_t)ent[u].y & 0x7fffffffu) << 32) | (uint32_t)ent[u].x;
+                r[u] = *reinterpret_cast<const Raw*>(p.x + row_off + load_off);
             }
-            if (live && p.out_h1) {
-                const int64_t j = wave + q * nw;
-                *reinterpret_cast<typename C::Raw*>(p.out_h1 + (b * k1 + j) * p.row_bytes + chunk_off) = C::pack(acc);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (i0 + u < my_len) {
+                    C::add(acc, r[u]);
+                    if (ent[u].y < 0) {                            // last row of its slot
+                        const int meta = flat_meta[my_start + i0 + u];
+                        const float inv = inv_count(meta >> 8);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) { acc[e] *= inv; root[e] += acc[e]; }
+                        if (live && p.out_h1)
+                            *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + (meta & 0xff)) * p.row_bytes + chunk_off) = C::pack(acc);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
+                    }
+                }
             }
         }
         for (int off = sub; off < kWave; off <<= 1) {
 #pragma unroll
             for (int e = 0; e < VE; ++e) root[e] += __shfl_xor(root[e], off);
+        }
+        if (nw == 1) {
+            if (sg == 0 && live) {
+                const int c1 = live_slots[0];
+                const float inv1 = inv_count(c1 > 0 ? c1 : 1);
+#pragma unroll
+                for (int e = 0; e < VE; ++e) root[e] *= inv1;
+                *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(root);
+            }
+            continue;
         }
         if (sg == 0) {
 #pragma unroll
@@ -220,10 +334,10 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
 #pragma unroll
                 for (int e = 0; e < VE; ++e) tot[e] += red[(w * sub + sl) * VE + e];
             }
-            const float fc1 = c1 > 0 ? (float)c1 : 1.0f;
+            const float inv1 = inv_count(c1 > 0 ? c1 : 1);
 #pragma unroll
-            for (int e = 0; e < VE; ++e) tot[e] = tot[e] / fc1;
-            *reinterpret_cast<typename C::Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(tot);
+            for (int e = 0; e < VE; ++e) tot[e] *= inv1;
+            *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(tot);
         }
         if (c0 + sub < p.chunks) __syncthreads();       // red is reused by the next tile
     }
@@ -237,15 +351,15 @@ static int env_int(const char* name, int fallback) {
     return v ? std::atoi(v) : fallback;
 }
 
-// Waves per root for the 2-hop kernel: enough sub-groups that every hop-1 slot is gathered
-// in one pass when that fits in 8 waves.
-int fwd2_waves(int k1, const RowGeom& g) {
+// Waves per root for the 2-hop kernel.  One wave per root keeps the most roots resident and
+// needs no block barrier; small batches are spread over more waves so that the chip still
+// holds about 16 waves per CU, and wide rows (several tiles per row) get more waves because
+// a single wave cannot keep enough row loads in flight.
+int fwd2_waves(int64_t B, int k1, const RowGeom& g) {
     static const int forced = env_int("FSA_FWD2_WAVES", 0);
     if (forced >= 1 && forced <= 8) return forced;
-    const int per_wave = kWave / g.sub;
-    int nw = (k1 + per_wave - 1) / per_wave;
-    if (nw < 1) nw = 1;
-    if (nw > 8) nw = 8;
+    int nw = 1;
+    while (nw < 8 && nw * 2 <= k1 && (B * nw < 4096 || g.tiles > nw)) nw *= 2;
     return nw;
 }
 
@@ -260,9 +374,9 @@ static hipError_t launch_typed(const FwdArgs& a, const FwdParams& p, hipStream_t
         if (replay) hipLaunchKernelGGL((fwd1_kernel<XT, VB, true>), dim3(grid), dim3(wpb * kWave), lds, stream, p);
         else        hipLaunchKernelGGL((fwd1_kernel<XT, VB, false>), dim3(grid), dim3(wpb * kWave), lds, stream, p);
     } else {
-        const int nw = fwd2_waves(a.k1, a.geom);
+        const int nw = fwd2_waves(a.B, a.k1, a.geom);
         const int nq_max = (a.k1 + nw - 1) / nw;
-        const size_t lds = sizeof(int) * ((size_t)nw * (nq_max * a.k2 + nq_max) + nw)
+        const size_t lds = sizeof(int) * ((size_t)nw * (4 * nq_max * a.k2 + 2 * nq_max) + nw)
                          + sizeof(float) * (size_t)nw * a.geom.sub * VE;
         if (replay) hipLaunchKernelGGL((fwd2_kernel<XT, VB, true>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
         else        hipLaunchKernelGGL((fwd2_kernel<XT, VB, false>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
