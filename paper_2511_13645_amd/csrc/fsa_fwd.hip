@@ -39,7 +39,16 @@ struct FwdParams {
     char* out; char* out_h1; int32_t* out_ids1; int32_t* out_ids2;
     int64_t B; int64_t row_bytes; uint64_t seed;
     int k1, k2, chunks, sub, sub_shift, indptr_is64;
+#ifdef FSA_TRACE
+    long long* trace;                       // debug builds: [B][8] wall-clock stamps (10 ns units)
+#endif
 };
+
+#ifdef FSA_TRACE
+#define FSA_STAMP(slot) do { if (p.trace && threadIdx.x == 0) p.trace[blockIdx.x * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define FSA_STAMP(slot) do { } while (0)
+#endif
 
 // Row start and length of node i: both indptr entries are requested before either is used.
 __device__ __forceinline__ void row_extent(const FwdParams& p, int64_t i, int64_t& start, int64_t& deg) {
@@ -150,118 +159,173 @@ void fwd2_kernel(const FwdParams p) {
     const int k1 = p.k1, k2 = p.k2;
 
     // LDS per wave: flat list of row byte offsets (int2, slot end flagged in bit 63)
-    // [nq_max*k2], leaf IDs by slot [nq_max*k2], slot-end records [nq_max*k2], per-slot count
-    // and flat offset [nq_max] each; then [nw] live-slot counts and [nw][sub*VE] floats for
-    // the cross-wave reduction.
+    // [nq_max*k2], slot-end records [nq_max*k2], leaf IDs by slot [nq_max*k2] and per-slot
+    // counts [nq_max] (both replay only), empty-slot list [nq_max]; then [nw] live-slot
+    // counts and [nw][sub*VE] floats for the cross-wave reduction.
     const int nq_max = (k1 + nw - 1) / nw;
     const int per_wave = 4 * nq_max * k2 + 2 * nq_max;            // even: int2 stays 8-byte aligned
     int2* flat = reinterpret_cast<int2*>(smem + wave * per_wave);
-    int* leaf = smem + wave * per_wave + 2 * nq_max * k2;
-    int* flat_meta = leaf + nq_max * k2;
-    int* cnt2 = flat_meta + nq_max * k2;
-    int* offs = cnt2 + nq_max;
+    int* flat_meta = smem + wave * per_wave + 2 * nq_max * k2;
+    int* leaf = flat_meta + nq_max * k2;
+    int* cnt2 = leaf + nq_max * k2;
+    int* empty_q = cnt2 + nq_max;
     int* live_slots = smem + nw * per_wave;
     float* red = reinterpret_cast<float*>(live_slots + nw);
 
     // hop 0, redundantly in every wave: lane j holds U[j]
+    FSA_STAMP(0);
     const int u_mine = hop0_id<REPLAY>(p, b, lane);
     if (!REPLAY && wave == 0 && p.out_ids1 && lane < k1) p.out_ids1[b * k1 + lane] = u_mine;
+    if (u_mine == 0x7ffffff0) FSA_STAMP(7);   // consume u_mine before the stamp
+    FSA_STAMP(1);
 
-    // owned slots: j = wave + q*nw, q < nq; lane q keeps slot q's node, row start and degree
+    // owned slots: j = wave + q*nw, q < nq; lane q keeps slot q's node, row start, degree, count
     const int nq = wave < k1 ? (k1 - wave + nw - 1) / nw : 0;
     const int u_own = __shfl(u_mine, lane < nq ? wave + lane * nw : 0);
-    int64_t s_own = 0, deg_own = 0;
-    if constexpr (!REPLAY) {
-        if (lane < nq && u_own >= 0) row_extent(p, u_own, s_own, deg_own);
-        if (lane < nq) cnt2[lane] = (int)(deg_own < (int64_t)k2 ? deg_own : (int64_t)k2);
-    }
-
-    // hop 1: (slot, step) pairs in passes of spw slots; loads of a pass group overlap
-    const int spw = kWave / k2;
+    const int spw = kWave / k2;                                   // slots handled per pass
     const int g = lane / k2;
     const int li = lane - g * k2;
-    for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {          // wave-uniform trip count
-        int idv[kPassGroup];
+    const uint64_t seg_mask = k2 == 64 ? ~0ull : ((1ull << k2) - 1ull);
+    int64_t s_own = 0;
+    uint32_t deg_own = 0;
+    int c_own = 0;
+    if constexpr (!REPLAY) {
+        if (lane < nq && u_own >= 0) {
+            int64_t d;
+            row_extent(p, u_own, s_own, d);
+            deg_own = (uint32_t)d;
+            c_own = (int)(d < (int64_t)k2 ? d : (int64_t)k2);
+        }
+    } else {
+        // saved leaf IDs of the owned slots: loads of a pass group overlap; holes are squeezed out
+        for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {       // wave-uniform trip count
+            int idv[kPassGroup];
 #pragma unroll
-        for (int t = 0; t < kPassGroup; ++t) {
-            idv[t] = -1;
-            if (q0 + t * spw < nq) {                               // wave-uniform
-                const int q = q0 + t * spw + g;
-                const bool valid = g < spw && q < nq;
-                const int src = valid ? q : 0;
-                const int u = __shfl(u_own, src);
-                const bool active = valid && u >= 0;
-                if constexpr (REPLAY) {
-                    if (active) idv[t] = p.ids2[(b * k1 + wave + q * nw) * k2 + li];
-                } else {
-                    const uint32_t s_lo = __shfl((uint32_t)s_own, src);
-                    const uint32_t s_hi = __shfl((uint32_t)((uint64_t)s_own >> 32), src);
-                    const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
-                    const int64_t deg = (int64_t)(uint32_t)__shfl((uint32_t)deg_own, src);
-                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
-                                                       deg, active, lane);
-                    if (pos >= 0) idv[t] = p.indices[s + pos];
+            for (int t = 0; t < kPassGroup; ++t) {
+                idv[t] = -1;
+                if (q0 + t * spw < nq) {
+                    const int q = q0 + t * spw + g;
+                    const bool valid = g < spw && q < nq;
+                    const int u = __shfl(u_own, valid ? q : 0);
+                    if (valid && u >= 0) idv[t] = p.ids2[(b * k1 + wave + q * nw) * k2 + li];
                 }
             }
-        }
 #pragma unroll
-        for (int t = 0; t < kPassGroup; ++t) {
-            if (q0 + t * spw < nq) {
-                const int q = q0 + t * spw + g;
-                const bool valid = g < spw && q < nq;
-                if constexpr (REPLAY) {
-                    const int seg_base = valid ? g * k2 : 0;
-                    const uint64_t seg = (k2 == 64 ? ~0ull : ((1ull << k2) - 1ull)) << seg_base;
-                    const uint64_t have = __ballot(valid && idv[t] >= 0) & seg;
+            for (int t = 0; t < kPassGroup; ++t) {
+                if (q0 + t * spw < nq) {
+                    const int q = q0 + t * spw + g;
+                    const bool valid = g < spw && q < nq;
+                    const uint64_t have = __ballot(valid && idv[t] >= 0) & (seg_mask << (valid ? g * k2 : 0));
                     if (valid && idv[t] >= 0) leaf[q * k2 + __popcll(have & lanemask_lt(lane))] = idv[t];
                     if (valid && li == 0) cnt2[q] = __popcll(have);
-                } else if (valid) {
-                    leaf[q * k2 + li] = idv[t];                    // valid IDs are a prefix of the slot
-                    if (p.out_ids2) p.out_ids2[(b * k1 + wave + q * nw) * k2 + li] = idv[t];
                 }
             }
         }
+        __builtin_amdgcn_wave_barrier();
+        if (lane < nq) c_own = cnt2[lane];
     }
-    __builtin_amdgcn_wave_barrier();
+    if (deg_own == 0x7ffffff0u) FSA_STAMP(7);
+    FSA_STAMP(2);
 
-    // flat lists: slot q goes to sub-group q % nsg; lists are stored back to back
+    // Where each slot's rows go in the flat list: exclusive prefix sum of the counts over
+    // lanes q.  Sub-group sg later walks the rows of a contiguous block of slots [qa, qb).
+    int incl = c_own;
+    for (int d = 1; d < nq; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    const int off_own = incl - c_own;
+    const int total = __shfl(incl, nq > 0 ? nq - 1 : 0);
+    const uint64_t empty_mask = __ballot(lane < nq && c_own == 0);
+    const int n_empty = __popcll(empty_mask);
+    if (lane < nq && c_own == 0) empty_q[__popcll(empty_mask & lanemask_lt(lane))] = lane;
+    if (lane == 0) live_slots[wave] = nq - n_empty;
+
     const int sub = p.sub;
     const int sg = lane >> p.sub_shift;
     const int sl = lane & (sub - 1);
     const int nsg = kWave >> p.sub_shift;
-    int my_start = 0, my_len = 0;        // this lane's sub-group list
-    {
-        int off_q = 0;                   // where slot `lane` starts (lanes < nq)
-        const int mq = lane & (nsg - 1);
-        for (int t = 0; t < nq; ++t) {
-            const int c = cnt2[t];
-            const int m = t & (nsg - 1);
-            my_start += m < sg ? c : 0;
-            my_len += m == sg ? c : 0;
-            off_q += (m < mq || (m == mq && t < lane)) ? c : 0;
-        }
-        if (lane < nq) offs[lane] = off_q;
-        const int mine = lane < nq ? cnt2[lane] : 0;
-        const int n_live = __popcll(__ballot(mine > 0));
-        if (lane == 0) live_slots[wave] = n_live;
+    // Row-balanced split: sub-group s takes the slots whose first row lies in
+    // [s*total/nsg, (s+1)*total/nsg); slots stay whole, so each sub-group is within one slot
+    // of an even share.  first_q(s) = number of slots starting before row s*total/nsg.
+    int qa = 0, qb = 0;
+    for (int s = 0; s <= nsg; ++s) {                               // wave-uniform
+        const int first_q = __popcll(__ballot(lane < nq && off_own * nsg < s * total));
+        if (s == sg) qa = first_q;
+        if (s == sg + 1) qb = first_q;
     }
-    __builtin_amdgcn_wave_barrier();
-    for (int q0 = 0; q0 < nq; q0 += spw) {
-        const int q = q0 + g;
-        if (g < spw && q < nq) {
-            const int c = cnt2[q];
-            if (li < c) {
-                const int at = offs[q] + li;
+    if (sg == nsg - 1) qb = nq;
+    const int start_a = __shfl(off_own, qa < nq ? qa : 0);
+    const int start_b = __shfl(off_own, qb < nq ? qb : 0);
+    const int my_start = qa < nq ? start_a : total;
+    const int my_len = (qb < nq ? start_b : total) - my_start;
+
+    if constexpr (!REPLAY) {
+        // hop 1: (slot, step) pairs in passes of spw slots.  The `indices` loads of a pass group
+        // are all issued before the first one is used; each sampled ID goes straight to its
+        // place in the flat list as a row byte offset.
+        for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {       // wave-uniform trip count
+            int idv[kPassGroup], dstv[kPassGroup];
+#pragma unroll
+            for (int t = 0; t < kPassGroup; ++t) {
+                idv[t] = -1;
+                dstv[t] = -1;
+                if (q0 + t * spw < nq) {                           // wave-uniform
+                    const int q = q0 + t * spw + g;
+                    const bool valid = g < spw && q < nq;
+                    const int src = valid ? q : 0;
+                    const int u = __shfl(u_own, src);
+                    const bool active = valid && u >= 0;
+                    const uint32_t s_lo = __shfl((uint32_t)s_own, src);
+                    const uint32_t s_hi = __shfl((uint32_t)((uint64_t)s_own >> 32), src);
+                    const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
+                    const int64_t deg = (int64_t)__shfl(deg_own, src);
+                    const int off = __shfl(off_own, src);
+                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
+                                                       deg, active, lane);
+                    if (pos >= 0) {
+                        idv[t] = p.indices[s + pos];
+                        const int c = (int)(deg < (int64_t)k2 ? deg : (int64_t)k2);
+                        dstv[t] = (off + li) | (li == c - 1 ? 0x40000000 : 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kPassGroup; ++t) {
+                if (q0 + t * spw < nq) {
+                    const int q = q0 + t * spw + g;
+                    const int j = wave + q * nw;
+                    if (g < spw && q < nq && p.out_ids2) p.out_ids2[(b * k1 + j) * k2 + li] = idv[t];
+                    if (dstv[t] >= 0) {
+                        const int at = dstv[t] & 0x3fffffff;
+                        const uint32_t last = (uint32_t)dstv[t] >> 30;
+                        const uint64_t row_off = (uint64_t)(uint32_t)idv[t] * (uint64_t)p.row_bytes;
+                        flat[at] = make_int2((int)(uint32_t)row_off, (int)((uint32_t)(row_off >> 32) | (last << 31)));
+                        if (last) flat_meta[at] = j | ((li + 1) << 8);
+                    }
+                }
+            }
+        }
+    } else {
+        for (int q0 = 0; q0 < nq; q0 += spw) {
+            const int q = q0 + g;
+            const bool valid = g < spw && q < nq;
+            const int off = __shfl(off_own, valid ? q : 0);
+            const int c = __shfl(c_own, valid ? q : 0);
+            if (valid && li < c) {
+                const int at = off + li;
+                const uint32_t last = li == c - 1 ? 1u : 0u;
                 const uint64_t row_off = (uint64_t)(uint32_t)leaf[q * k2 + li] * (uint64_t)p.row_bytes;
-                flat[at] = make_int2((int)(uint32_t)row_off,
-                                     (int)((uint32_t)(row_off >> 32) | (li == c - 1 ? 0x80000000u : 0u)));
-                if (li == c - 1) flat_meta[at] = (wave + q * nw) | (c << 8);
+                flat[at] = make_int2((int)(uint32_t)row_off, (int)((uint32_t)(row_off >> 32) | (last << 31)));
+                if (last) flat_meta[at] = (wave + q * nw) | (c << 8);
             }
         }
     }
     __builtin_amdgcn_wave_barrier();
+    FSA_STAMP(3);
 
     // gather
+    FSA_STAMP(4);
     for (int c0 = 0; c0 < p.chunks; c0 += sub) {
         const int chunk = c0 + sl;
         const bool live = chunk < p.chunks;
@@ -270,9 +334,8 @@ void fwd2_kernel(const FwdParams p) {
 #pragma unroll
         for (int e = 0; e < VE; ++e) { acc[e] = 0.0f; root[e] = 0.0f; }
         if (p.out_h1 && live) {                                    // empty slots get zero rows
-            for (int q = sg; q < nq; q += nsg)
-                if (cnt2[q] == 0)
-                    *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + wave + q * nw) * p.row_bytes + chunk_off) = C::pack(acc);
+            for (int i = sg; i < n_empty; i += nsg)
+                *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + wave + empty_q[i] * nw) * p.row_bytes + chunk_off) = C::pack(acc);
         }
         // Row loads carry no branch of their own: past the end of the list they re-read its
         // last row (a cache hit) and lanes beyond the row width re-read chunk 0; the results
@@ -309,6 +372,7 @@ void fwd2_kernel(const FwdParams p) {
 #pragma unroll
             for (int e = 0; e < VE; ++e) root[e] += __shfl_xor(root[e], off);
         }
+        FSA_STAMP(5);
         if (nw == 1) {
             if (sg == 0 && live) {
                 const int c1 = live_slots[0];
@@ -393,6 +457,9 @@ hipError_t launch_forward(const FwdArgs& a, hipStream_t stream) {
     p.B = a.B; p.row_bytes = a.D * (a.x_is_bf16 ? 2 : 4); p.seed = a.seed;
     p.k1 = a.k1; p.k2 = a.k2; p.chunks = a.geom.chunks; p.sub = a.geom.sub;
     p.sub_shift = __builtin_ctz((unsigned)a.geom.sub); p.indptr_is64 = a.indptr_is64;
+#ifdef FSA_TRACE
+    { const char* t = std::getenv("FSA_TRACE_PTR"); p.trace = t ? reinterpret_cast<long long*>(std::strtoull(t, nullptr, 16)) : nullptr; }
+#endif
     const int vb = a.geom.vec_bytes;
     if (a.x_is_bf16) {
         switch (vb) {
