@@ -45,6 +45,35 @@ def algorithmic_bytes(leaf_rows, hop1_rows, B, k1, k2, D, elem, iptr, emit_ids=T
     return b
 
 
+def load_or_make_workload(name, scale, cache, dev):
+    """The seeded workload, generated on the GPU, or the same bytes re-read from raw files."""
+    import numpy as np
+    import torch
+    from paper_2511_13645_amd import synth
+    tdt = {"int32": torch.int32, "int64": torch.int64, "float32": torch.float32, "bfloat16": torch.bfloat16}
+    ndt = {"int32": np.int32, "int64": np.int64, "float32": np.float32, "bfloat16": np.int16}
+    meta_path = os.path.join(cache, "meta.json") if cache else ""
+    if cache and os.path.exists(meta_path):
+        m = json.load(open(meta_path))
+        if m["name"] != name or m["scale"] != scale:
+            raise RuntimeError("cache %s holds %s at scale %g" % (cache, m["name"], m["scale"]))
+
+        def rd(fn, dt, shape):
+            t = torch.from_numpy(np.fromfile(os.path.join(cache, fn), dtype=ndt[dt]).reshape(shape)).to(dev)
+            return t.view(torch.bfloat16) if dt == "bfloat16" else t
+        g = synth.Graph(rd("indptr.bin", m["indptr"], (m["N"] + 1,)), rd("indices.bin", "int32", (m["E"],)), m["N"])
+        return synth.Workload(name, g, rd("x.bin", m["x"], (m["N"], m["D"])), m["B"], tuple(m["fan"]), m["seed"])
+    w = synth.make_workload(name, device=dev, scale=scale)
+    if cache:
+        os.makedirs(cache, exist_ok=True)
+        for fn, t in (("indptr.bin", w.graph.indptr), ("indices.bin", w.graph.indices), ("x.bin", w.x)):
+            (t.view(torch.int16) if t.dtype == torch.bfloat16 else t).cpu().numpy().tofile(os.path.join(cache, fn))
+        json.dump({"name": name, "scale": scale, "N": w.graph.num_nodes, "E": w.graph.num_edges, "D": w.x.shape[1],
+                   "indptr": str(w.graph.indptr.dtype).split(".")[1], "x": str(w.x.dtype).split(".")[1],
+                   "B": w.batch, "fan": list(w.fanouts), "seed": w.sampler_seed}, open(meta_path, "w"))
+    return w
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +84,13 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="CPU time budget of the oracle leg (0 = skip)")
     ap.add_argument("--no-emit", action="store_true", help="do not emit IDs / per-slot means")
+    ap.add_argument("--saturated-batch", type=int, default=65536,
+                    help="also time a few launches at this batch size on the same graph (0 = skip)")
+    ap.add_argument("--cache", default="", help="directory with raw copies of the workload: written if "
+                    "absent, loaded if present (counter runs use it: rocprofv3 --pmc does not survive the "
+                    "in-process generation of the full-size graph on this image)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU by scope (no sharding, no collectives); "
@@ -71,8 +107,16 @@ def main() -> int:
     dev = "cuda:0"
     L = binding.lib()
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     t0 = time.time()
-    w = synth.make_workload(args.workload, device=dev, scale=args.scale)
+    w = load_or_make_workload(args.workload, args.scale, args.cache, dev)
     torch.cuda.synchronize()
     g, x = w.graph, w.x
     B = args.batch or w.batch
@@ -91,21 +135,25 @@ def main() -> int:
     emit = not args.no_emit
     out = torch.empty((B, D), dtype=x.dtype, device=dev)
     out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev) if (hops == 2 and emit) else None
-    ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev) if emit else None
-    ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev) if (hops == 2 and emit) else None
+    # every launch emits its IDs into its own slice, so the rows it aggregated can be counted
+    # after the timed region without launching anything else
+    n_id = (steps + warmup) if emit else 1
+    ids1 = torch.empty((n_id, B, k1), dtype=torch.int32, device=dev)
+    ids2 = torch.empty((n_id, B, k1, k2), dtype=torch.int32, device=dev) if hops == 2 else None
 
     fan_host = (ctypes.c_int32 * hops)(*fan)
     stream = torch.cuda.current_stream().cuda_stream
     fixed_head = (g.indptr.data_ptr(), binding.FSA_I64 if iptr == 8 else binding.FSA_I32, g.indices.data_ptr(), N,
                   x.data_ptr(), binding.FSA_BF16 if x.dtype == torch.bfloat16 else binding.FSA_F32, D)
-    fixed_tail = (B, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed,
-                  out.data_ptr(), None if out_h1 is None else out_h1.data_ptr(),
-                  None if ids1 is None else ids1.data_ptr(), None if ids2 is None else ids2.data_ptr(), stream)
+    fixed_mid = (B, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed,
+                 out.data_ptr(), None if out_h1 is None else out_h1.data_ptr())
     seed_ptrs = [seeds[i].data_ptr() for i in range(steps + warmup)]
+    id1_ptrs = [ids1[i].data_ptr() if emit else None for i in range(steps + warmup)]
+    id2_ptrs = [ids2[i].data_ptr() if (emit and hops == 2) else None for i in range(steps + warmup)]
     fwd = L.fsa_sample_mean_fwd
 
     def step(i):
-        rc = fwd(*fixed_head, seed_ptrs[i], *fixed_tail)
+        rc = fwd(*fixed_head, seed_ptrs[i], *fixed_mid, id1_ptrs[i], id2_ptrs[i], stream)
         if rc != 0:
             raise RuntimeError("fsa_sample_mean_fwd -> %d" % rc)
 
@@ -124,17 +172,26 @@ def main() -> int:
     ms_per_step = wall * 1e3 / steps
     kern_ms = ev_ms / steps
 
-    # what the timed launches actually aggregated (untimed recount of the same batches)
+    # what the timed launches actually aggregated
     leaf_rows = 0
     hop1_rows = 0
-    for i in range(warmup, warmup + steps):
-        o, h, i1, i2 = binding.fsa_sample_mean_fwd(g.indptr, g.indices, x, seeds[i], fan, w.sampler_seed,
-                                                   emit_h1=False, emit_ids=True)
+    if emit:
         if hops == 2:
-            leaf_rows += int((i2 >= 0).sum().item())
-            hop1_rows += int((i1 >= 0).sum().item())
+            leaf_rows = int((ids2[warmup:] >= 0).sum().item())
+            hop1_rows = int((ids1[warmup:] >= 0).sum().item())
         else:
-            leaf_rows += int((i1 >= 0).sum().item())
+            leaf_rows = int((ids1[warmup:] >= 0).sum().item())
+    else:                            # nothing was emitted: count with untimed emitting launches
+        for i in range(warmup, warmup + steps):
+            rc = fwd(*fixed_head, seed_ptrs[i], *fixed_mid[:-1], None, ids1[0].data_ptr(),
+                     ids2[0].data_ptr() if hops == 2 else None, stream)
+            if rc != 0:
+                raise RuntimeError("fsa_sample_mean_fwd -> %d" % rc)
+            if hops == 2:
+                leaf_rows += int((ids2[0] >= 0).sum().item())
+                hop1_rows += int((ids1[0] >= 0).sum().item())
+            else:
+                leaf_rows += int((ids1[0] >= 0).sum().item())
     if hops == 2:
         alg = algorithmic_bytes(leaf_rows, hop1_rows, B * steps, k1, k2, D, elem, iptr, emit, emit)
     else:
@@ -152,6 +209,36 @@ def main() -> int:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
+
+    saturated = None
+    if args.saturated_batch > 0 and hops == 2:
+        Bs, n_sat = args.saturated_batch, 20
+        s_seeds = synth.seed_batches(N, Bs, n_sat + 2, seed=5).to(dev)
+        s_out = torch.empty((Bs, D), dtype=x.dtype, device=dev)
+        s_h1 = torch.empty((Bs, k1, D), dtype=x.dtype, device=dev) if emit else None
+        s_i1 = torch.empty((Bs, k1), dtype=torch.int32, device=dev) if emit else None
+        s_i2 = torch.empty((Bs, k1, k2), dtype=torch.int32, device=dev) if emit else None
+        tail = (Bs, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed, s_out.data_ptr(),
+                None if s_h1 is None else s_h1.data_ptr(), None if s_i1 is None else s_i1.data_ptr(),
+                None if s_i2 is None else s_i2.data_ptr(), stream)
+        for i in range(2):
+            fwd(*fixed_head, s_seeds[i].data_ptr(), *tail)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(2, n_sat + 2):
+            fwd(*fixed_head, s_seeds[i].data_ptr(), *tail)
+        e1.record()
+        torch.cuda.synchronize()
+        s_ms = e0.elapsed_time(e1) / n_sat
+        o, h, i1, i2 = binding.fsa_sample_mean_fwd(g.indptr, g.indices, x, s_seeds[2], fan, w.sampler_seed, emit_h1=False)
+        s_leaf, s_hop1 = int((i2 >= 0).sum().item()), int((i1 >= 0).sum().item())
+        s_alg = algorithmic_bytes(s_leaf, s_hop1, Bs, k1, k2, D, elem, iptr, emit, emit)
+        saturated = {"global_batch": Bs, "launch_us": s_ms * 1e3, "rows_per_s": s_leaf / (s_ms * 1e-3),
+                     "hbm_gbps": s_alg / (s_ms * 1e-3) / 1e9, "frac": s_alg / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        del s_seeds, s_out, s_h1, s_i1, s_i2
+        log("[bench] B=%d: %.1f us/launch, %.2f G rows/s, %.0f GB/s algorithmic" %
+            (Bs, s_ms * 1e3, saturated["rows_per_s"] / 1e9, saturated["hbm_gbps"]))
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -194,6 +281,7 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "kernel": "fwd2_kernel" if hops == 2 else "fwd1_kernel", "launch_us": kern_ms * 1e3},
         "cpu_baseline": cpu,
+        "saturated": saturated,
     }
     print(json.dumps(line), flush=True)
     return 0

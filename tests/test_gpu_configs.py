@@ -1,0 +1,118 @@
+"""GPU parity at the full sizes of the five workload shapes, in the launch configuration the
+benchmark times.  Graphs and tables are generated on the GPU from the seeded recipes and the
+very same bytes are copied to the host for the oracle."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from parity_util import TOL, assert_close, assert_ids_equal, forward_scales, host_x, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def fsa():
+    from paper_2511_13645_amd import binding
+    binding.lib()
+    return binding
+
+
+def _build(name):
+    from paper_2511_13645_amd import synth
+    t0 = time.time()
+    w = synth.make_workload(name, device="cuda:0")
+    torch.cuda.synchronize()
+    seeds = synth.seed_batches(w.graph.num_nodes, w.batch, 1, seed=2)[0]
+    print("[%s] N=%d E=%d D=%d built in %.1fs" % (name, w.graph.num_nodes, w.graph.num_edges, w.x.shape[1],
+                                                   time.time() - t0), flush=True)
+    return w, seeds
+
+
+def _forward_parity(fsa, orc, w, seeds, what):
+    fan = list(w.fanouts)
+    g, x = w.graph, w.x
+    d_seeds = seeds.cuda()
+    out, h1, ids1, ids2 = fsa.fsa_sample_mean_fwd(g.indptr, g.indices, x, d_seeds, fan, w.sampler_seed)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    h_indptr, h_indices = g.indptr.cpu().numpy(), g.indices.cpu().numpy()
+    hx, is_bf16 = host_x(x)
+    t1 = time.time()
+    r_out, r_h1, r_ids1, r_ids2 = orc.sample_mean_fwd(h_indptr, h_indices, hx, seeds.numpy(), fan, w.sampler_seed,
+                                                      bf16=is_bf16)
+    print("[%s] host copy %.1fs, oracle forward %.1fs" % (what, t1 - t0, time.time() - t1), flush=True)
+    assert_ids_equal(ids1, r_ids1, what + " ids1")
+    if len(fan) == 2:
+        assert_ids_equal(ids2, r_ids2, what + " ids2")
+    a_out, a_h1 = forward_scales(x, ids1, ids2)
+    tol = TOL[x.dtype]
+    worst = assert_close(to_f64(out), r_out, a_out, tol, what + " out")
+    if len(fan) == 2:
+        worst = max(worst, assert_close(to_f64(h1), r_h1, a_h1, tol, what + " out_h1"))
+    print("[%s] ids bit-exact; worst relative error of the means %.2e (bound %.0e)" % (what, worst, tol), flush=True)
+    rp_out, rp_h1 = fsa.fsa_mean_replay_fwd(x, ids1, ids2)
+    torch.cuda.synchronize()
+    assert torch.equal(rp_out.view(torch.uint8), out.view(torch.uint8)), what + " replay out differs"
+    if len(fan) == 2:
+        assert torch.equal(rp_h1.view(torch.uint8), h1.view(torch.uint8)), what + " replay h1 differs"
+    return ids1, ids2, r_ids1, r_ids2
+
+
+def _backward_parity(fsa, orc, w, ids1, ids2, r_ids1, r_ids2, what, with_h1):
+    from paper_2511_13645_amd import synth
+    N, D = w.x.shape
+    B, k1 = ids1.shape
+    g = synth.upstream_grad((B, D), seed=3, device="cuda:0")
+    gh = synth.upstream_grad((B, k1, D), seed=4, device="cuda:0") if with_h1 else None
+    gx = torch.zeros((N, D), dtype=torch.float32, device="cuda:0")
+    fsa.fsa_mean_bwd(g, ids1, ids2, gh, grad_x=gx)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    r_gx = orc.mean_bwd(to_f64(g), r_ids1, r_ids2, None if gh is None else to_f64(gh), num_nodes=N)
+    scale = orc.mean_bwd(np.abs(to_f64(g)), r_ids1, r_ids2, None if gh is None else np.abs(to_f64(gh)), num_nodes=N)
+    print("[%s] oracle backward %.1fs" % (what, time.time() - t0), flush=True)
+    touched = np.unique(np.concatenate([r_ids2[r_ids2 >= 0]]) if r_ids2 is not None else r_ids1[r_ids1 >= 0])
+    got = gx[torch.from_numpy(touched).cuda().long()].double().cpu().numpy()
+    worst = assert_close(got, r_gx[touched], scale[touched], 1e-5, what + " grad_x (touched rows)")
+    # rows nobody sampled stay exactly zero
+    total = float(gx.double().abs().sum().item())
+    assert abs(total - np.abs(got).sum()) <= 1e-6 * max(1.0, total), what + " gradient leaked outside the sampled rows"
+    print("[%s] grad_x over %d touched rows: worst relative error %.2e" % (what, touched.size, worst), flush=True)
+
+
+def test_products_shape_two_hop_forward(fsa, orc):
+    """N=2,449,029, ~123.7M edges, x[N,100] fp32, B=1024, fanouts [15,10], forward only."""
+    w, seeds = _build("products")
+    assert w.graph.num_nodes == 2_449_029 and abs(w.graph.num_edges / 123.7e6 - 1) < 0.03
+    _forward_parity(fsa, orc, w, seeds, "products")
+
+
+def test_social_shape_two_hop_forward_backward(fsa, orc):
+    """N=232,965, ~114.6M edges (mean ~492), x[N,602] fp32, B=1024, fanouts [25,10], fwd + bwd."""
+    w, seeds = _build("social")
+    assert w.graph.num_nodes == 232_965 and abs(w.graph.num_edges / 114.6e6 - 1) < 0.03
+    ids = _forward_parity(fsa, orc, w, seeds, "social")
+    _backward_parity(fsa, orc, w, *ids, "social", with_h1=True)
+
+
+def test_kg_shape_one_hop_training(fsa, orc):
+    """2.5M entities, 16.1M triples both directions, x[N,128] fp32 U(-0.1,0.1), B=4096, k=15."""
+    w, seeds = _build("kg")
+    assert w.graph.num_nodes == 2_500_000 and w.graph.num_edges == 32_200_000
+    assert w.graph.degrees().max().item() > 1_000_000       # the Zipf(1.1) hub
+    hub = int(torch.argmax(w.graph.degrees()).item())
+    seeds = seeds.clone()
+    seeds[0] = hub                                           # make sure the longest row is sampled
+    ids1, ids2, r_ids1, r_ids2 = _forward_parity(fsa, orc, w, seeds, "kg")
+    _backward_parity(fsa, orc, w, ids1, None, r_ids1, None, "kg", with_h1=False)
+
+
+def test_citation_shape_two_hop_forward_bf16_wide_indptr(fsa, orc):
+    """N=111M, ~1.6B edges, int64 indptr, x[N,128] bf16 (~28 GB), B=4096, fanouts [15,10]."""
+    w, seeds = _build("citation")
+    assert w.graph.num_nodes == 111_000_000 and w.graph.indptr.dtype == torch.int64
+    assert w.graph.num_edges > 2**31 - 1 or abs(w.graph.num_edges / 1.6e9 - 1) < 0.05
+    assert w.x.dtype == torch.bfloat16
+    _forward_parity(fsa, orc, w, seeds, "citation")
