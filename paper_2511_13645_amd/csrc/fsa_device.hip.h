@@ -51,23 +51,30 @@ __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane
 // Returns this lane's position inside the row (0-based), or -1 for an unused slot.
 // deg <= k keeps the whole row in CSR order (Sec. 3.2: t = min(k, |N(v)|)).
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, uint32_t hop,
-                                                  int k, int li, int seg_base, int64_t deg,
-                                                  bool active, int lane) {
+// The draw of Floyd step li for a row of length deg (only meaningful when deg > k).
+__device__ __forceinline__ uint32_t floyd_draw(uint64_t seed, uint32_t node, uint32_t hop, int k,
+                                               int li, int64_t deg) {
+    const uint32_t r = philox4x32_10_word0(node, hop, (uint32_t)li, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
+    return __umulhi(r, (uint32_t)(deg - k) + (uint32_t)li + 1u);    // uniform in [0, J_li]
+}
+
+// Turn the draws of a segment into positions (see above).  `t` is this lane's draw.
+__device__ __forceinline__ int64_t floyd_resolve(uint32_t t, int k, int li, int seg_base, int64_t deg,
+                                                 bool active, int lane) {
     const bool floyd = active && deg > (int64_t)k;
-    uint32_t t = 0u;
     const uint32_t base = floyd ? (uint32_t)(deg - k) : 0u;          // J_i = base + li
-    if (floyd) {
-        const uint32_t r = philox4x32_10_word0(node, hop, (uint32_t)li, 0u,
-                                               (uint32_t)seed, (uint32_t)(seed >> 32));
-        t = __umulhi(r, base + (uint32_t)li + 1u);                   // uniform in [0, J_i]
-    }
+    if (!floyd) t = 0xffffffffu - (uint32_t)lane;                    // never equal to a real draw's partner
     bool collided = false;
     if (__any(floyd)) {                                              // wave-uniform
+        // duplicate of an earlier draw of the same segment; shuffles issued eight at a time so
+        // that their latencies overlap (steps beyond k or beyond li never match the m < li test)
         bool dup_earlier = false;
-        for (int m = 0; m < k; ++m) {
-            const uint32_t tm = (uint32_t)__shfl((int)t, seg_base + m);
-            dup_earlier = dup_earlier || (m < li && tm == t);
+        for (int m0 = 0; m0 < k; m0 += 8) {
+            uint32_t tm[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) tm[j] = (uint32_t)__shfl((int)t, seg_base + m0 + j);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) dup_earlier = dup_earlier || (m0 + j < li && tm[j] == t);
         }
         const bool hits_J = floyd && t >= base && (t - base) < (uint32_t)li;
         const int dep_lane = seg_base + (int)(t - base);
@@ -84,6 +91,14 @@ __device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, 
     }
     if (floyd) return collided ? (int64_t)(base + (uint32_t)li) : (int64_t)t;
     return (active && (int64_t)li < deg) ? (int64_t)li : -1;
+}
+
+__device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, uint32_t hop,
+                                                  int k, int li, int seg_base, int64_t deg,
+                                                  bool active, int lane) {
+    uint32_t t = 0u;
+    if (__any(active && deg > (int64_t)k)) t = floyd_draw(seed, node, hop, k, li, deg);   // wave-uniform
+    return floyd_resolve(t, k, li, seg_base, deg, active, lane);
 }
 
 template <typename IT>

@@ -266,6 +266,24 @@ void fwd2_kernel(const FwdParams p) {
         // place in the flat list as a row byte offset.
         for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {       // wave-uniform trip count
             int idv[kPassGroup], dstv[kPassGroup];
+            uint32_t draw[kPassGroup];
+            int degv[kPassGroup];                                  // -1: lane has no row in this pass
+            // stage A: the draws of every pass that holds a row longer than the fanout
+#pragma unroll
+            for (int t = 0; t < kPassGroup; ++t) {
+                degv[t] = -1;
+                draw[t] = 0u;
+                if (q0 + t * spw >= nq) continue;                  // wave-uniform
+                const int q = q0 + t * spw + g;
+                const bool valid = g < spw && q < nq;
+                const int src = valid ? q : 0;
+                const int u = __shfl(u_own, src);
+                const int deg = (int)__shfl(deg_own, src);
+                degv[t] = (valid && u >= 0) ? deg : -1;
+                if (__any(degv[t] > k2))                           // wave-uniform
+                    draw[t] = floyd_draw(p.seed, (uint32_t)u, 1u, k2, li, (int64_t)deg);
+            }
+            // stage B: positions, then the `indices` loads of all passes in flight together
 #pragma unroll
             for (int t = 0; t < kPassGroup; ++t) {
                 idv[t] = -1;
@@ -274,16 +292,13 @@ void fwd2_kernel(const FwdParams p) {
                     const int q = q0 + t * spw + g;
                     const bool valid = g < spw && q < nq;
                     const int src = valid ? q : 0;
-                    const int u = __shfl(u_own, src);
-                    const bool active = valid && u >= 0;
+                    const int64_t deg = (int64_t)degv[t];
+                    const int64_t pos = floyd_resolve(draw[t], k2, li, valid ? g * k2 : 0, deg, degv[t] >= 0, lane);
                     const uint32_t s_lo = __shfl((uint32_t)s_own, src);
                     const uint32_t s_hi = __shfl((uint32_t)((uint64_t)s_own >> 32), src);
-                    const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
-                    const int64_t deg = (int64_t)__shfl(deg_own, src);
                     const int off = __shfl(off_own, src);
-                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
-                                                       deg, active, lane);
                     if (pos >= 0) {
+                        const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
                         idv[t] = p.indices[s + pos];
                         const int c = (int)(deg < (int64_t)k2 ? deg : (int64_t)k2);
                         dstv[t] = (off + li) | (li == c - 1 ? 0x40000000 : 0);
@@ -416,14 +431,14 @@ static int env_int(const char* name, int fallback) {
 }
 
 // Waves per root for the 2-hop kernel.  One wave per root keeps the most roots resident and
-// needs no block barrier; small batches are spread over more waves so that the chip still
-// holds about 16 waves per CU, and wide rows (several tiles per row) get more waves because
-// a single wave cannot keep enough row loads in flight.
-int fwd2_waves(int64_t B, int k1, const RowGeom& g) {
+// needs no block barrier; small batches are spread over more waves (which then own fewer
+// hop-1 slots each) until the chip holds about 16 waves per CU.  Measured on the product,
+// social and citation shapes at B = 1024 .. 65536.
+int fwd2_waves(int64_t B, int k1, const RowGeom&) {
     static const int forced = env_int("FSA_FWD2_WAVES", 0);
     if (forced >= 1 && forced <= 8) return forced;
     int nw = 1;
-    while (nw < 8 && nw * 2 <= k1 && (B * nw < 4096 || g.tiles > nw)) nw *= 2;
+    while (nw < 8 && nw * 2 <= k1 && B * nw < 4096) nw *= 2;
     return nw;
 }
 
