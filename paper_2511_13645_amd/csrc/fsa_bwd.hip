@@ -30,40 +30,151 @@ __device__ __forceinline__ void merge_equal_ids(int id, int k, int li, int seg_b
                                                 bool& first) {
     mult = 0;
     first = true;
-    for (int m = 0; m < k; ++m) {
-        const int other = __shfl(id, seg_base + m);
-        if (other == id) { ++mult; if (m < li) first = false; }
+    for (int m0 = 0; m0 < k; m0 += 8) {                 // eight shuffles in flight at a time
+        int other[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) other[j] = __shfl(id, seg_base + m0 + j);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (m0 + j < k && other[j] == id) { ++mult; if (m0 + j < li) first = false; }
+        }
     }
 }
 
-__global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p) {
+// ---------------------------------------------------------------------------------------
+// 1-hop backward.  A workgroup of 4 waves takes 4*spw consecutive seeds (wave w the seeds
+// w, w+4, ...).  Rows that many seeds of the workgroup share -- the hub rows of a skewed
+// graph, which would otherwise serialise thousands of atomics on one L2 channel -- are first
+// summed in LDS and reach grad_x with ONE atomic row-add per workgroup:
+//   pass 1  every sampled ID bumps an LDS counter at hash(id);
+//   pass 2  the count threshold is doubled from kHotMin until no more buckets reach it than
+//           there are LDS rows; IDs in such buckets claim them (first claimant wins; a
+//           colliding ID simply stays on the direct path) and claimed buckets get an LDS row;
+//   pass 3  per seed: equal IDs of the seed are merged (multiplicity), then each distinct row
+//           receives grad_out[b,:] * mult/cnt -- into its LDS row if it owns a bucket, else
+//           straight into grad_x with hardware fp32 atomics, 256 contiguous bytes per wave
+//           instruction;
+//   flush   LDS rows are added to grad_x.
+// When no counter reaches kHotMin (uniform graphs) passes 2 and flush are skipped.
+// ---------------------------------------------------------------------------------------
+constexpr int kHotBuckets = 2048;
+constexpr int kHotMin = 3;
+constexpr int kHotRowsMax = 64;
+
+__device__ __forceinline__ int hot_hash(int id) {
+    return (int)(((uint32_t)id * 2654435761u) >> 21);              // 11 bits -> kHotBuckets
+}
+
+__global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p, int spw, int hot_rows) {
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (b >= p.B) return;                               // wave-uniform, no block barrier below
-    int* rows = smem + wave * 2 * kWave;
+    const int nw = blockDim.x >> 6;
+    // LDS: counters, tags, row-of-bucket [kHotBuckets] each; [2] flags; node of each LDS row
+    // [kHotRowsMax]; per wave [64] rows + [64] weights + [64] hot-row index; then hot_rows * D
+    // floats.
+    int* count = smem;
+    int* tag = count + kHotBuckets;
+    int* row_of = tag + kHotBuckets;
+    int* flags = row_of + kHotBuckets;                               // [0] any hot, [1] rows handed out
+    int* row_node = flags + 2;
+    int* rows = row_node + kHotRowsMax + wave * 3 * kWave;
     float* weight = reinterpret_cast<float*>(rows + kWave);
+    int* hot_of = rows + 2 * kWave;
+    float* hot = reinterpret_cast<float*>(row_node + kHotRowsMax + nw * 3 * kWave);
+    const int64_t b0 = (int64_t)blockIdx.x * nw * spw;
 
-    const int id = lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
-    const int cnt = __popcll(__ballot(id >= 0));
-    int mult; bool first;
-    merge_equal_ids(id, p.k1, lane, 0, mult, first);
-    const bool keep = id >= 0 && first;
-    const uint64_t kept = __ballot(keep);
-    const int n = __popcll(kept);
-    if (keep) {
-        const int slot = __popcll(kept & lanemask_lt(lane));
-        rows[slot] = id;
-        weight[slot] = (float)mult / (float)cnt;
+    for (int i = threadIdx.x; i < kHotBuckets; i += blockDim.x) { count[i] = 0; tag[i] = -1; row_of[i] = -1; }
+    if (threadIdx.x < 2) flags[threadIdx.x] = 0;
+    __syncthreads();
+
+    // pass 1: count IDs per bucket (lanes cover consecutive entries of the workgroup's seeds)
+    const bool use_hot = hot_rows > 0;
+    if (use_hot) {
+        const int64_t first = b0 * p.k1;
+        const int64_t n_ent = ((b0 + (int64_t)nw * spw < p.B ? b0 + (int64_t)nw * spw : p.B) - b0) * p.k1;
+        bool saw_hot = false;
+        for (int64_t e = threadIdx.x; e < n_ent; e += blockDim.x) {
+            const int id = p.ids1[first + e];
+            if (id >= 0) saw_hot = (atomicAdd(&count[hot_hash(id)], 1) + 1 >= kHotMin) || saw_hot;
+        }
+        if (saw_hot) flags[0] = 1;
+        __syncthreads();
+        if (flags[0]) {                                              // workgroup-uniform
+            // pass 2: the busiest buckets, as many as there are LDS rows
+            int thresh = kHotMin;
+            for (;;) {                                               // workgroup-uniform trip count
+                int mine = 0;
+                for (int i = threadIdx.x; i < kHotBuckets; i += blockDim.x) mine += count[i] >= thresh;
+                if (mine) atomicAdd(&flags[1], mine);
+                __syncthreads();
+                const int n_over = flags[1];
+                __syncthreads();
+                if (threadIdx.x == 0) flags[1] = 0;
+                __syncthreads();
+                if (n_over <= hot_rows) break;
+                thresh *= 2;
+            }
+            for (int64_t e = threadIdx.x; e < n_ent; e += blockDim.x) {
+                const int id = p.ids1[first + e];
+                if (id >= 0 && count[hot_hash(id)] >= thresh) atomicCAS(&tag[hot_hash(id)], -1, id);
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < kHotBuckets; i += blockDim.x) {
+                if (tag[i] >= 0) {                                   // at most hot_rows buckets qualify
+                    const int r = atomicAdd(&flags[1], 1);
+                    row_of[i] = r;
+                    row_node[r] = tag[i];
+                }
+            }
+            __syncthreads();
+            const int n_rows = flags[1];
+            for (int64_t i = threadIdx.x; i < (int64_t)n_rows * p.D; i += blockDim.x) hot[i] = 0.0f;
+            __syncthreads();
+        }
     }
-    __builtin_amdgcn_wave_barrier();
-    for (int64_t d0 = 0; d0 < p.D; d0 += kWave) {
-        const int64_t d = d0 + lane;
-        if (d < p.D) {
-            const float g = p.grad_out[b * p.D + d];
-            for (int e = 0; e < n; ++e)
-                atomic_add_f32(p.grad_x + (int64_t)rows[e] * p.D + d, g * weight[e]);
+    const bool any_hot = use_hot && flags[0] != 0;
+
+    // pass 3: one seed at a time per wave
+    for (int s = 0; s < spw; ++s) {
+        const int64_t b = b0 + wave + (int64_t)s * nw;
+        if (b >= p.B) break;                                         // wave-uniform
+        const int id = lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
+        const int cnt = __popcll(__ballot(id >= 0));
+        int mult; bool first;
+        merge_equal_ids(id, p.k1, lane, 0, mult, first);
+        const bool keep = id >= 0 && first;
+        const uint64_t kept = __ballot(keep);
+        const int n = __popcll(kept);
+        if (keep) {
+            const int slot = __popcll(kept & lanemask_lt(lane));
+            rows[slot] = id;
+            weight[slot] = (float)mult / (float)cnt;
+            int hr = -1;
+            if (any_hot) { const int h = hot_hash(id); if (tag[h] == id) hr = row_of[h]; }
+            hot_of[slot] = hr;
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int64_t d0 = 0; d0 < p.D; d0 += kWave) {
+            const int64_t d = d0 + lane;
+            if (d < p.D) {
+                const float g = p.grad_out[b * p.D + d];
+                for (int e = 0; e < n; ++e) {
+                    const int hr = hot_of[e];
+                    if (hr >= 0) atomicAdd(&hot[(int64_t)hr * p.D + d], g * weight[e]);
+                    else atomic_add_f32(p.grad_x + (int64_t)rows[e] * p.D + d, g * weight[e]);
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    if (any_hot) {                                                   // workgroup-uniform
+        __syncthreads();
+        const int n_rows = flags[1];
+        for (int r = wave; r < n_rows; r += nw) {
+            float* dst = p.grad_x + (int64_t)row_node[r] * p.D;
+            for (int64_t d = lane; d < p.D; d += kWave) atomic_add_f32(dst + d, hot[(int64_t)r * p.D + d]);
         }
     }
 }
@@ -152,10 +263,20 @@ hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
     p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
     p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
     if (!a.ids2) {
-        const int wpb = 4;
-        const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
-        hipLaunchKernelGGL(bwd1_kernel, dim3(grid), dim3(wpb * kWave), sizeof(int) * 2 * kWave * wpb,
-                           stream, p);
+        // seeds per wave: more seeds per workgroup merge more hub traffic, but small batches
+        // must still spread over the chip
+        static const int forced_spw = env_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
+        const int nw = 4;
+        int spw = 2;
+        while (spw < 16 && a.B / (spw * 2) >= 4096) spw *= 2;   // 2 up to B=16k, 16 from B=64k
+        if (forced_spw >= 1 && forced_spw <= 64) spw = forced_spw;
+        int hot_rows = (int)(8192 / a.D);                    // at most 32 KB of LDS rows
+        if (hot_rows > kHotRowsMax) hot_rows = kHotRowsMax;
+        static const int no_hot = env_int("FSA_BWD1_NO_HOT", 0);
+        if (no_hot) hot_rows = 0;
+        const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
+        const size_t lds = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave) + sizeof(float) * (size_t)hot_rows * a.D;
+        hipLaunchKernelGGL(bwd1_kernel, dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
     } else {
         static const int forced = env_int("FSA_BWD2_WAVES", 0);
         int nw = (forced >= 1 && forced <= 8) ? forced : (a.k1 < 8 ? a.k1 : 8);
