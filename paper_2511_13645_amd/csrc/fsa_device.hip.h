@@ -63,7 +63,6 @@ __device__ __forceinline__ int64_t floyd_resolve(uint32_t t, int k, int li, int 
                                                  bool active, int lane) {
     const bool floyd = active && deg > (int64_t)k;
     const uint32_t base = floyd ? (uint32_t)(deg - k) : 0u;          // J_i = base + li
-    if (!floyd) t = 0xffffffffu - (uint32_t)lane;                    // never equal to a real draw's partner
     bool collided = false;
     if (__any(floyd)) {                                              // wave-uniform
         // duplicate of an earlier draw of the same segment; shuffles issued eight at a time so

@@ -7,13 +7,15 @@
 //          a wave-private LDS strip; the wave is cut into 64/sub sub-groups of `sub` lanes,
 //          each sub-group covers one feature row with 16/8/4-byte loads and the sub-groups
 //          take different neighbor rows, so several rows are in flight per instruction.
-//   2-hop: one workgroup per root.  Every wave redraws the root's hop-1 IDs (k1 lanes, no
-//          block barrier needed) and owns the hop-1 slots j = wave, wave+W, ...; it samples
-//          their rows in segments of k2 lanes (64/k2 rows at once), stages the leaf IDs in
-//          its own LDS strip and then gathers them, one sub-group per slot, keeping each
-//          slot's sum in registers.  Slot means go straight to out_h1; the root mean is
-//          reduced across sub-groups by shuffles and across waves through LDS, and written
-//          once.  No [B,k,D] gathered tensor and no block structure ever exists.
+//   2-hop: one workgroup per root, by default a single wave (more waves, each owning a
+//          subset of the hop-1 slots, only for small batches).  The wave draws the hop-1
+//          IDs (k1 lanes), reads their row extents (one lane per slot), samples their rows
+//          in segments of k2 lanes (64/k2 rows per pass) and writes every sampled leaf ID
+//          straight into a flat, row-balanced list in LDS; sub-groups then stream the
+//          listed rows eight loads deep, closing a slot (mean -> out_h1, add to the root
+//          sum) whenever a flagged entry goes by.  The root mean is reduced by shuffles
+//          (and through LDS across waves) and written once.  No [B,k,D] gathered tensor
+//          and no block structure ever exists.
 // The replay kernels are the same code with the sampler swapped for loads of the saved IDs,
 // which is what makes replay bitwise equal to the sampling forward.
 #include "fsa_device.hip.h"
@@ -135,12 +137,13 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
 // indices -> feature rows); at the paper's batch sizes the launch is about as long as that
 // chain, so the kernel is laid out to take each step ONCE per wave, for all of its slots:
 //   step 1-3  hop 0 (every wave redraws it; lanes j < k1 end with U[j]);
-//   step 4    lane q reads the indptr pair of owned slot q (all slots in one go);
+//   step 4    lane q reads the indptr pair of owned slot q (all slots in one go); a scan of
+//             the slot counts fixes where each slot's rows go in the flat list;
 //   step 5    Floyd positions for (slot, step) pairs, 64/k2 slots per pass, with the
-//             `indices` loads of up to kPassGroup passes in flight together;
-//   step 6    the leaf IDs of all owned slots are laid out as one flat list per sub-group
-//             (slot ends flagged in bit 31), so that the row loads run kUnroll deep across
-//             slot boundaries instead of one slot at a time.
+//             `indices` loads of up to kPassGroup passes in flight together; each ID is
+//             stored as a 64-bit row byte offset, slot ends flagged in bit 63;
+//   step 6    sub-groups walk contiguous, row-balanced blocks of the list, kUnroll row
+//             loads in flight across slot boundaries instead of one slot at a time.
 // ---------------------------------------------------------------------------------------
 constexpr int kPassGroup = FSA_PASS_GROUP;
 

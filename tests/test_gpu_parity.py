@@ -233,3 +233,21 @@ def test_ids_do_not_depend_on_batching_or_stream(fsa):
         assert torch.equal(side[i], full[i])
     other = fsa.fsa_sample_mean_fwd(d_indptr, d_indices, x, seeds, [15, 10], 8)
     assert not torch.equal(other[3], full[3])
+
+
+@pytest.mark.parametrize("n_targets,B", [(3, 700), (100, 4096), (1000, 20000)])
+def test_backward_with_heavily_shared_rows(fsa, orc, n_targets, B):
+    """Every row of the graph points into the same small set of nodes, so the seeds of a
+    workgroup keep hitting the same rows: exercises the in-LDS aggregation of shared rows in
+    the 1-hop backward (more shared rows than LDS rows when n_targets is large)."""
+    rng = np.random.default_rng(n_targets)
+    n, D, k = 30000, 96, 15
+    deg = rng.integers(0, 40, size=n)
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    hot = rng.permutation(n)[:n_targets]
+    p = 1.0 / np.arange(1, n_targets + 1) ** 1.2
+    indices = hot[rng.choice(n_targets, size=int(indptr[-1]), p=p / p.sum())].astype(np.int32)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    seeds = rng.integers(0, n, B).astype(np.int32)
+    run_case(fsa, orc, indptr, indices, x, seeds, [k], 3, what="shared rows %d" % n_targets)
+    run_case(fsa, orc, indptr, indices, x, seeds[:777], [5, 4], 3, what="shared rows 2-hop %d" % n_targets)
