@@ -6,6 +6,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifndef FSA_DUP_CHUNK
+#define FSA_DUP_CHUNK 4      // shuffles issued together in the duplicate test
+#endif
+
 namespace fsa {
 
 constexpr int kWave = 64;
@@ -65,15 +69,15 @@ __device__ __forceinline__ int64_t floyd_resolve(uint32_t t, int k, int li, int 
     const uint32_t base = floyd ? (uint32_t)(deg - k) : 0u;          // J_i = base + li
     bool collided = false;
     if (__any(floyd)) {                                              // wave-uniform
-        // duplicate of an earlier draw of the same segment; shuffles issued eight at a time so
+        // duplicate of an earlier draw of the same segment; shuffles issued a few at a time so
         // that their latencies overlap (steps beyond k or beyond li never match the m < li test)
         bool dup_earlier = false;
-        for (int m0 = 0; m0 < k; m0 += 8) {
-            uint32_t tm[8];
+        for (int m0 = 0; m0 < k; m0 += FSA_DUP_CHUNK) {
+            uint32_t tm[FSA_DUP_CHUNK];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) tm[j] = (uint32_t)__shfl((int)t, seg_base + m0 + j);
+            for (int j = 0; j < FSA_DUP_CHUNK; ++j) tm[j] = (uint32_t)__shfl((int)t, seg_base + m0 + j);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) dup_earlier = dup_earlier || (m0 + j < li && tm[j] == t);
+            for (int j = 0; j < FSA_DUP_CHUNK; ++j) dup_earlier = dup_earlier || (m0 + j < li && tm[j] == t);
         }
         const bool hits_J = floyd && t >= base && (t - base) < (uint32_t)li;
         const int dep_lane = seg_base + (int)(t - base);

@@ -269,24 +269,6 @@ void fwd2_kernel(const FwdParams p) {
         // place in the flat list as a row byte offset.
         for (int q0 = 0; q0 < nq; q0 += kPassGroup * spw) {       // wave-uniform trip count
             int idv[kPassGroup], dstv[kPassGroup];
-            uint32_t draw[kPassGroup];
-            int degv[kPassGroup];                                  // -1: lane has no row in this pass
-            // stage A: the draws of every pass that holds a row longer than the fanout
-#pragma unroll
-            for (int t = 0; t < kPassGroup; ++t) {
-                degv[t] = -1;
-                draw[t] = 0u;
-                if (q0 + t * spw >= nq) continue;                  // wave-uniform
-                const int q = q0 + t * spw + g;
-                const bool valid = g < spw && q < nq;
-                const int src = valid ? q : 0;
-                const int u = __shfl(u_own, src);
-                const int deg = (int)__shfl(deg_own, src);
-                degv[t] = (valid && u >= 0) ? deg : -1;
-                if (__any(degv[t] > k2))                           // wave-uniform
-                    draw[t] = floyd_draw(p.seed, (uint32_t)u, 1u, k2, li, (int64_t)deg);
-            }
-            // stage B: positions, then the `indices` loads of all passes in flight together
 #pragma unroll
             for (int t = 0; t < kPassGroup; ++t) {
                 idv[t] = -1;
@@ -295,13 +277,16 @@ void fwd2_kernel(const FwdParams p) {
                     const int q = q0 + t * spw + g;
                     const bool valid = g < spw && q < nq;
                     const int src = valid ? q : 0;
-                    const int64_t deg = (int64_t)degv[t];
-                    const int64_t pos = floyd_resolve(draw[t], k2, li, valid ? g * k2 : 0, deg, degv[t] >= 0, lane);
+                    const int u = __shfl(u_own, src);
+                    const bool active = valid && u >= 0;
                     const uint32_t s_lo = __shfl((uint32_t)s_own, src);
                     const uint32_t s_hi = __shfl((uint32_t)((uint64_t)s_own >> 32), src);
+                    const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
+                    const int64_t deg = (int64_t)__shfl(deg_own, src);
                     const int off = __shfl(off_own, src);
+                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
+                                                       deg, active, lane);
                     if (pos >= 0) {
-                        const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
                         idv[t] = p.indices[s + pos];
                         const int c = (int)(deg < (int64_t)k2 ? deg : (int64_t)k2);
                         dstv[t] = (off + li) | (li == c - 1 ? 0x40000000 : 0);
