@@ -116,3 +116,29 @@ def test_citation_shape_two_hop_forward_bf16_wide_indptr(fsa, orc):
     assert w.graph.num_edges > 2**31 - 1 or abs(w.graph.num_edges / 1.6e9 - 1) < 0.05
     assert w.x.dtype == torch.bfloat16
     _forward_parity(fsa, orc, w, seeds, "citation")
+
+
+def test_row_offsets_beyond_32_bits(fsa, orc):
+    """A CSR whose `indices` array has more than 2^31 entries: row starts need the int64 indptr
+    path end to end (the citation shape stays just below 2^31 entries)."""
+    from paper_2511_13645_amd import synth
+    dev = "cuda:0"
+    n, deg, D = 300_000, 7_400, 32
+    E = n * deg
+    assert E > 2**31
+    indptr = torch.arange(0, E + 1, deg, dtype=torch.int64, device=dev)
+    indices = torch.empty(E, dtype=torch.int32, device=dev)
+    step = 1 << 28
+    for e0 in range(0, E, step):
+        e1 = min(E, e0 + step)
+        idx = torch.arange(e0, e1, dtype=torch.int64, device=dev)
+        indices[e0:e1] = (synth.hash64(7, 0, idx) % n).abs().to(torch.int32)
+        del idx
+    x = synth.features(n, D, seed=1, device=dev)
+    # seeds from the top of the ID range, whose rows start beyond 2^31 (and 2^32 / 4 bytes)
+    seeds = torch.cat([torch.arange(n - 300, n, dtype=torch.int32), synth.seed_batches(n, 212, 1, seed=2)[0]])
+    assert int(indptr[seeds[0].item()].item()) > 2**31
+    w = synth.Workload("wide", synth.Graph(indptr, indices, n), x, seeds.shape[0], (15, 10))
+    _forward_parity(fsa, orc, w, seeds, "wide offsets")
+    w1 = synth.Workload("wide", w.graph, x, seeds.shape[0], (20,))
+    _forward_parity(fsa, orc, w1, seeds, "wide offsets 1-hop")
