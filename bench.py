@@ -7,7 +7,9 @@ aggregated per second and achieved HBM GB/s at fanout 15/10, D = 128) is quoted 
 is one launch of the fused 2-hop forward with ID and per-slot emission over a fresh batch of
 seeds; inputs are resident in HBM before the timed region starts.
 
-Prints ONE JSON line (see the design doc for every field).  `--gpus N` with N > 1 is refused: this
+Prints ONE JSON line: throughput, roofline block (algorithmic bytes per launch over the launch
+duration by HIP events, against the 8 TB/s HBM peak), oracle CPU baseline and a saturated-batch
+block.  `--gpus N` with N > 1 is refused: this
 build is single-GPU by scope.
 """
 from __future__ import annotations

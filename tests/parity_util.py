@@ -1,6 +1,6 @@
 """Helpers for the GPU parity tests: host copies for the oracle, tolerance scales, compare.
 
-Tolerances (the benchmark spec): sampled IDs bit-exact; means and gradients within
+Tolerances: sampled IDs bit-exact; means and gradients within
 max relative error 1e-5 (fp32 features) / 1e-2 (bf16 features).  "Relative" is taken
 against max(|ref|, A): A is the mean magnitude of the rows that were averaged (forward) or
 the sum of the magnitudes of the contributions (backward), so that an output that is small
