@@ -63,6 +63,13 @@ def lib() -> ctypes.CDLL:
         L.orc_mean_replay_fwd.restype = ctypes.c_int
         L.orc_mean_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64]
         L.orc_mean_bwd.restype = ctypes.c_int
+        L.orc_sample_wmean_fwd.argtypes = [vp, ctypes.c_int, vp, vp, i64, vp, ctypes.c_int, i64,
+                                           vp, i64, vp, ctypes.c_int, u64, vp, vp, vp, vp, vp, vp]
+        L.orc_sample_wmean_fwd.restype = ctypes.c_int
+        L.orc_wmean_replay_fwd.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp, vp, vp, i64, i32, i32, vp, vp]
+        L.orc_wmean_replay_fwd.restype = ctypes.c_int
+        L.orc_wmean_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, vp, i64]
+        L.orc_wmean_bwd.restype = ctypes.c_int
         L.orc_round_to_bf16.argtypes = [vp, i64, vp]
         L.orc_round_to_bf16.restype = None
         L.orc_round_to_f32.argtypes = [vp, i64, vp]
@@ -192,6 +199,73 @@ def mean_bwd(grad_out, ids1, ids2=None, grad_h1=None, *, num_nodes: int, grad_x=
                             _vp(grad_x), num_nodes)
     if rc != 0:
         raise ValueError("orc_mean_bwd failed with %d" % rc)
+    return grad_x
+
+
+def sample_wmean_fwd(indptr, indices, edge_weight, x, seeds, fanouts, seed, *, bf16=False):
+    """Weighted variant.  Returns (out, out_h1 | None, ids1, ids2 | None, w1, w2 | None)."""
+    indptr = _c(indptr)
+    indices = _c(indices, np.int32)
+    edge_weight = _c(edge_weight, np.float32)
+    x = _c(x)
+    seeds = _c(seeds, np.int32)
+    fan = np.asarray(list(fanouts), dtype=np.int32)
+    hops = int(fan.size)
+    N, D, B = indptr.shape[0] - 1, x.shape[1], seeds.shape[0]
+    k1 = int(fan[0])
+    k2 = int(fan[1]) if hops == 2 else 0
+    out = np.zeros((B, D), dtype=np.float64)
+    out_h1 = np.zeros((B, k1, D), dtype=np.float64) if hops == 2 else None
+    ids1 = np.full((B, k1), -7, dtype=np.int32)
+    ids2 = np.full((B, k1, k2), -7, dtype=np.int32) if hops == 2 else None
+    w1 = np.full((B, k1), -7, dtype=np.float32)
+    w2 = np.full((B, k1, k2), -7, dtype=np.float32) if hops == 2 else None
+    rc = lib().orc_sample_wmean_fwd(_vp(indptr), _indptr_type(indptr), _vp(indices), _vp(edge_weight), N,
+                                    _vp(x), _x_type(x, bf16), D, _vp(seeds), B, _vp(fan), hops, seed,
+                                    _vp(out), _vp(out_h1), _vp(ids1), _vp(ids2), _vp(w1), _vp(w2))
+    if rc != 0:
+        raise ValueError("orc_sample_wmean_fwd failed with %d" % rc)
+    return out, out_h1, ids1, ids2, w1, w2
+
+
+def wmean_replay_fwd(x, ids1, w1, ids2=None, w2=None, *, bf16=False):
+    x = _c(x)
+    ids1 = _c(ids1, np.int32)
+    w1 = _c(w1, np.float32)
+    B, k1 = ids1.shape
+    D = x.shape[1]
+    k2 = 0
+    if ids2 is not None:
+        ids2 = _c(ids2, np.int32)
+        w2 = _c(w2, np.float32)
+        k2 = ids2.shape[2]
+    out = np.zeros((B, D), dtype=np.float64)
+    out_h1 = np.zeros((B, k1, D), dtype=np.float64) if ids2 is not None else None
+    rc = lib().orc_wmean_replay_fwd(_vp(x), _x_type(x, bf16), D, x.shape[0], _vp(ids1), _vp(ids2), _vp(w1),
+                                    _vp(w2), B, k1, k2, _vp(out), _vp(out_h1))
+    if rc != 0:
+        raise ValueError("orc_wmean_replay_fwd failed with %d" % rc)
+    return out, out_h1
+
+
+def wmean_bwd(grad_out, ids1, w1, ids2=None, w2=None, grad_h1=None, *, num_nodes: int):
+    grad_out = _c(grad_out, np.float64)
+    ids1 = _c(ids1, np.int32)
+    w1 = _c(w1, np.float32)
+    B, k1 = ids1.shape
+    D = grad_out.shape[1]
+    k2 = 0
+    if ids2 is not None:
+        ids2 = _c(ids2, np.int32)
+        w2 = _c(w2, np.float32)
+        k2 = ids2.shape[2]
+    if grad_h1 is not None:
+        grad_h1 = _c(grad_h1, np.float64)
+    grad_x = np.zeros((num_nodes, D), dtype=np.float64)
+    rc = lib().orc_wmean_bwd(_vp(grad_out), _vp(grad_h1), _vp(ids1), _vp(ids2), _vp(w1), _vp(w2), B, k1, k2, D,
+                             _vp(grad_x), num_nodes)
+    if rc != 0:
+        raise ValueError("orc_wmean_bwd failed with %d" % rc)
     return grad_x
 
 

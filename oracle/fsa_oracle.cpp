@@ -271,6 +271,157 @@ int orc_mean_bwd(const double* grad_out, const double* grad_h1,
     return 0;
 }
 
+// ---- weighted mean ----------------------------------------------------------------------
+// Sec. 3.2 "Extension Feasibility": weighted numerators and denominators per sampled
+// neighborhood.  Written out as the plain definition over the sampled (ID, weight) pairs.
+static double weighted_mean_of_rows(const void* x, int dtype, int64_t D, const int32_t* ids,
+                                    const float* w, int32_t k, double* dst) {
+    for (int64_t d = 0; d < D; ++d) dst[d] = 0.0;
+    double total = 0.0;
+    for (int32_t i = 0; i < k; ++i)
+        if (ids[i] >= 0) total += static_cast<double>(w[i]);
+    if (!(total > 0.0)) return 0.0;
+    for (int32_t i = 0; i < k; ++i) {
+        if (ids[i] < 0) continue;
+        const double wi = static_cast<double>(w[i]);
+        for (int64_t d = 0; d < D; ++d) dst[d] += wi * read_x(x, dtype, ids[i], D, d);
+    }
+    for (int64_t d = 0; d < D; ++d) dst[d] /= total;
+    return total;
+}
+
+int orc_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const float* w1, const float* w2,
+                         int64_t B, int32_t k1, int32_t k2, double* out, double* out_h1) {
+    if (!x || !ids1 || !w1 || !out) return -1;
+    if (B < 0 || D <= 0 || k1 <= 0 || num_nodes <= 0) return -2;
+    if (ids2 && (k2 <= 0 || !w2)) return -2;
+    std::vector<double> inner(static_cast<size_t>(D));
+    for (int64_t b = 0; b < B; ++b) {
+        double* out_b = out + b * D;
+        if (!ids2) {
+            weighted_mean_of_rows(x, x_dtype, D, ids1 + b * k1, w1 + b * k1, k1, out_b);
+            continue;
+        }
+        for (int64_t d = 0; d < D; ++d) out_b[d] = 0.0;
+        double outer_total = 0.0;
+        for (int32_t j = 0; j < k1; ++j) {
+            double inner_total = 0.0;
+            if (ids1[b * k1 + j] >= 0) {
+                inner_total = weighted_mean_of_rows(x, x_dtype, D, ids2 + (b * k1 + j) * k2,
+                                                    w2 + (b * k1 + j) * k2, k2, inner.data());
+            } else {
+                for (int64_t d = 0; d < D; ++d) inner[d] = 0.0;
+            }
+            if (out_h1) std::memcpy(out_h1 + (b * k1 + j) * D, inner.data(), sizeof(double) * D);
+            if (inner_total > 0.0) {
+                const double a = static_cast<double>(w1[b * k1 + j]);
+                outer_total += a;
+                for (int64_t d = 0; d < D; ++d) out_b[d] += a * inner[d];
+            }
+        }
+        if (outer_total > 0.0) {
+            for (int64_t d = 0; d < D; ++d) out_b[d] /= outer_total;
+        } else {
+            for (int64_t d = 0; d < D; ++d) out_b[d] = 0.0;
+        }
+    }
+    return 0;
+}
+
+int orc_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         const float* edge_weight, int64_t num_nodes,
+                         const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                         uint64_t seed, double* out, double* out_h1,
+                         int32_t* ids1, int32_t* ids2, float* w1, float* w2) {
+    if (!indptr || !indices || !edge_weight || !x || !seeds || !fanouts || !out) return -1;
+    if (num_hops != 1 && num_hops != 2) return -2;
+    if (B < 0 || D <= 0 || num_nodes <= 0) return -2;
+    const int32_t k1 = fanouts[0];
+    const int32_t k2 = (num_hops == 2) ? fanouts[1] : 0;
+    if (k1 <= 0 || (num_hops == 2 && k2 <= 0)) return -2;
+    // sample IDs and pick up the weight of every sampled edge slot, then average as in replay
+    std::vector<int32_t> U(static_cast<size_t>(B) * k1, -1), W;
+    std::vector<float> A(static_cast<size_t>(B) * k1, 0.0f), Wt;
+    if (num_hops == 2) {
+        W.assign(static_cast<size_t>(B) * k1 * k2, -1);
+        Wt.assign(static_cast<size_t>(B) * k1 * k2, 0.0f);
+    }
+    std::vector<int64_t> pos(static_cast<size_t>(k1 > k2 ? k1 : k2));
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t r = seeds[b];
+        if (r < 0 || r >= num_nodes) return -2;
+        const int32_t c1 = orc_sample_row(indptr, indptr_type, indices, r, 0u, k1, seed, pos.data(), &U[b * k1]);
+        const int64_t s0 = read_indptr(indptr, indptr_type, r);
+        for (int32_t j = 0; j < c1; ++j) A[b * k1 + j] = edge_weight[s0 + pos[j]];
+        if (num_hops == 1) continue;
+        for (int32_t j = 0; j < c1; ++j) {
+            const int64_t u = U[b * k1 + j];
+            const int32_t c2 = orc_sample_row(indptr, indptr_type, indices, u, 1u, k2, seed, pos.data(),
+                                              &W[(b * k1 + j) * k2]);
+            const int64_t s1 = read_indptr(indptr, indptr_type, u);
+            for (int32_t i = 0; i < c2; ++i) Wt[(b * k1 + j) * k2 + i] = edge_weight[s1 + pos[i]];
+        }
+    }
+    if (ids1) std::memcpy(ids1, U.data(), sizeof(int32_t) * U.size());
+    if (w1) std::memcpy(w1, A.data(), sizeof(float) * A.size());
+    if (num_hops == 2) {
+        if (ids2) std::memcpy(ids2, W.data(), sizeof(int32_t) * W.size());
+        if (w2) std::memcpy(w2, Wt.data(), sizeof(float) * Wt.size());
+    }
+    return orc_wmean_replay_fwd(x, x_dtype, D, num_nodes, U.data(), num_hops == 2 ? W.data() : nullptr,
+                                A.data(), num_hops == 2 ? Wt.data() : nullptr, B, k1, k2, out, out_h1);
+}
+
+// Adjoint of the weighted replay forward with respect to X (weights are data, not variables).
+int orc_wmean_bwd(const double* grad_out, const double* grad_h1,
+                  const int32_t* ids1, const int32_t* ids2, const float* w1, const float* w2,
+                  int64_t B, int32_t k1, int32_t k2, int64_t D, double* grad_x, int64_t num_nodes) {
+    if (!grad_out || !ids1 || !w1 || !grad_x) return -1;
+    if (B < 0 || D <= 0 || k1 <= 0 || num_nodes <= 0) return -2;
+    if (ids2 && (k2 <= 0 || !w2)) return -2;
+    for (int64_t b = 0; b < B; ++b) {
+        const double* g_b = grad_out + b * D;
+        if (!ids2) {
+            double total = 0.0;
+            for (int32_t i = 0; i < k1; ++i)
+                if (ids1[b * k1 + i] >= 0) total += static_cast<double>(w1[b * k1 + i]);
+            if (!(total > 0.0)) continue;
+            for (int32_t i = 0; i < k1; ++i) {
+                const int32_t u = ids1[b * k1 + i];
+                if (u < 0) continue;
+                const double share = static_cast<double>(w1[b * k1 + i]) / total;
+                for (int64_t d = 0; d < D; ++d) grad_x[static_cast<int64_t>(u) * D + d] += g_b[d] * share;
+            }
+            continue;
+        }
+        std::vector<double> inner_total(static_cast<size_t>(k1), 0.0);
+        double outer_total = 0.0;
+        for (int32_t j = 0; j < k1; ++j) {
+            if (ids1[b * k1 + j] < 0) continue;
+            for (int32_t i = 0; i < k2; ++i)
+                if (ids2[(b * k1 + j) * k2 + i] >= 0) inner_total[j] += static_cast<double>(w2[(b * k1 + j) * k2 + i]);
+            if (inner_total[j] > 0.0) outer_total += static_cast<double>(w1[b * k1 + j]);
+        }
+        for (int32_t j = 0; j < k1; ++j) {
+            if (!(inner_total[j] > 0.0)) continue;
+            const double outer_share = outer_total > 0.0 ? static_cast<double>(w1[b * k1 + j]) / outer_total : 0.0;
+            for (int32_t i = 0; i < k2; ++i) {
+                const int32_t w = ids2[(b * k1 + j) * k2 + i];
+                if (w < 0) continue;
+                const double share = static_cast<double>(w2[(b * k1 + j) * k2 + i]) / inner_total[j];
+                for (int64_t d = 0; d < D; ++d) {
+                    double g = g_b[d] * outer_share;
+                    if (grad_h1) g += grad_h1[(b * k1 + j) * D + d];
+                    grad_x[static_cast<int64_t>(w) * D + d] += g * share;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
 // Round-to-nearest-even from double straight to the 8-bit significand of bfloat16.
 void orc_round_to_bf16(const double* src, int64_t n, uint16_t* dst) {
     for (int64_t i = 0; i < n; ++i) {

@@ -86,6 +86,31 @@ int orc_mean_bwd(const double* grad_out, const double* grad_h1,
                  int64_t B, int32_t k1, int32_t k2, int64_t D,
                  double* grad_x, int64_t num_nodes);
 
+/* ---- weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted
+ * numerators and denominators streamed per sampled neighborhood) -------------------------
+ * edge_weight [E] fp32, aligned with `indices`, non-negative and finite.  Sampling is
+ * unchanged (uniform over edge slots); only the average is weighted:
+ *   1-hop  out[b] = sum_i w1[b,i] X[ids1[b,i]] / W,  W = sum_i w1[b,i];  W == 0 -> zero row
+ *   2-hop  inner_j = sum_i w2[b,j,i] X[ids2[b,j,i]] / W2_j;  slot j takes part iff
+ *          ids1[b,j] >= 0 and W2_j > 0;  out[b] = sum_j w1[b,j] inner_j / sum_j w1[b,j]
+ *          over the slots that take part (zero row if that divisor is 0).
+ * The forward emits the weight of every sampled edge (w1 [B,k1], w2 [B,k1,k2], 0 in unused
+ * slots); replay and backward take them back together with the IDs.  Parity pins: unit
+ * weights reproduce the unweighted functions bit for bit; a fanout >= every degree reduces
+ * to weighted-adjacency products computed by scipy; finite differences for the backward. */
+int orc_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         const float* edge_weight, int64_t num_nodes,
+                         const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                         uint64_t seed, double* out, double* out_h1,
+                         int32_t* ids1, int32_t* ids2, float* w1, float* w2);
+int orc_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const float* w1, const float* w2,
+                         int64_t B, int32_t k1, int32_t k2, double* out, double* out_h1);
+int orc_wmean_bwd(const double* grad_out, const double* grad_h1,
+                  const int32_t* ids1, const int32_t* ids2, const float* w1, const float* w2,
+                  int64_t B, int32_t k1, int32_t k2, int64_t D, double* grad_x, int64_t num_nodes);
+
 /* Round fp64 values to bfloat16 bit patterns / fp32, round-to-nearest-even, directly from
  * the double (no intermediate float rounding). */
 void orc_round_to_bf16(const double* src, int64_t n, uint16_t* dst);
