@@ -113,6 +113,47 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
                  int64_t B, int32_t k1, int32_t k2, int64_t D,
                  float* grad_x, int64_t num_nodes, void* stream);
 
+/*
+ * Weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted numerators
+ * and denominators streamed per sampled neighborhood).  edge_weight [E] fp32 is aligned with
+ * `indices`; weights must be finite and non-negative.  Sampling is unchanged -- the same
+ * draws and the same IDs as fsa_sample_mean_fwd for the same seed -- only the average is
+ * weighted:
+ *   1-hop  out[b] = sum_i w1[b,i] X[ids1[b,i]] / W_b,  W_b = sum_i w1[b,i];  W_b == 0 -> zero row
+ *   2-hop  inner_j = sum_i w2[b,j,i] X[ids2[b,j,i]] / W2_bj;  slot j takes part iff
+ *          ids1[b,j] >= 0 and W2_bj > 0;  out[b] = sum_j w1[b,j] inner_j / sum_j w1[b,j] over
+ *          the slots that take part (zero row when that divisor is 0); out_h1[b,j,:] = inner_j
+ *          (zero row for a slot that does not take part).
+ * The sampling forward emits the weight of every sampled edge slot next to its ID
+ * (out_w1 [B,k1], out_w2 [B,k1,k2], fp32, 0 in unused slots; each may be NULL); replay and
+ * backward take the weights back together with the IDs.  Unit weights give the unweighted
+ * means.  Everything else (layouts, stream, status codes, B == 0) is as for the unweighted
+ * entry points; replay is bitwise equal to the sampling forward.
+ *   backward 1-hop:  grad_x[ids1[b,i],:] += grad_out[b,:] * w1[b,i] / W_b
+ *   backward 2-hop:  grad_x[ids2[b,j,i],:] += (grad_out[b,:] * w1[b,j] / A_b + grad_h1[b,j,:])
+ *                                              * w2[b,j,i] / W2_bj,   A_b = sum of w1 over the
+ *                    slots that take part (the first term is dropped when A_b == 0).
+ */
+int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         const float* edge_weight, int64_t num_nodes,
+                         const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                         uint64_t seed, void* out, void* out_h1,
+                         int32_t* out_ids1, int32_t* out_ids2, float* out_w1, float* out_w2,
+                         void* stream);
+
+int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2,
+                         const float* w1, const float* w2,
+                         int64_t B, int32_t k1, int32_t k2,
+                         void* out, void* out_h1, void* stream);
+
+int fsa_wmean_bwd(const float* grad_out, const float* grad_h1,
+                  const int32_t* ids1, const int32_t* ids2,
+                  const float* w1, const float* w2,
+                  int64_t B, int32_t k1, int32_t k2, int64_t D,
+                  float* grad_x, int64_t num_nodes, void* stream);
+
 /* Static, never-freed description of a status code. */
 const char* fsa_status_string(int status);
 

@@ -21,7 +21,8 @@ FSA_I32, FSA_I64 = 0, 1
 FSA_OK = 0
 FSA_KMAX = 64
 
-EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_status_string")
+EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_status_string",
+           "fsa_sample_wmean_fwd", "fsa_wmean_replay_fwd", "fsa_wmean_bwd")
 
 _lib: Optional[ctypes.CDLL] = None
 
@@ -47,6 +48,13 @@ def lib() -> ctypes.CDLL:
         L.fsa_mean_replay_fwd.restype = ci
         L.fsa_mean_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
         L.fsa_mean_bwd.restype = ci
+        L.fsa_sample_wmean_fwd.argtypes = [vp, ci, vp, vp, i64, vp, ci, i64, vp, i64, vp, ci, u64,
+                                           vp, vp, vp, vp, vp, vp, vp]
+        L.fsa_sample_wmean_fwd.restype = ci
+        L.fsa_wmean_replay_fwd.argtypes = [vp, ci, i64, i64, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.fsa_wmean_replay_fwd.restype = ci
+        L.fsa_wmean_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
+        L.fsa_wmean_bwd.restype = ci
         L.fsa_status_string.argtypes = [ci]
         L.fsa_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -179,4 +187,79 @@ def fsa_mean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torc
                             _ptr(grad_x), N, _stream(stream))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd")
+    return grad_x
+
+
+def fsa_sample_wmean_fwd(indptr: torch.Tensor, indices: torch.Tensor, edge_weight: torch.Tensor, x: torch.Tensor,
+                         seeds: torch.Tensor, fanouts: Sequence[int], seed: int, *,
+                         emit_h1: bool = True, emit_ids: bool = True,
+                         stream: Optional[torch.cuda.Stream] = None):
+    """Weighted fused sample + mean.  Returns (out, out_h1, ids1, ids2, w1, w2); IDs and weights
+    are emitted together (emit_ids), entries not asked for are None."""
+    _need(indptr, "indptr"); _need(indices, "indices", torch.int32); _need(x, "x")
+    _need(seeds, "seeds", torch.int32); _need(edge_weight, "edge_weight", torch.float32)
+    if edge_weight.shape[0] != indices.shape[0]:
+        raise ValueError("edge_weight must have one entry per CSR entry")
+    fan = [int(k) for k in fanouts]
+    hops = len(fan)
+    B, (N, D) = seeds.shape[0], x.shape
+    dev = x.device
+    k1 = fan[0] if hops >= 1 else 0
+    k2 = fan[1] if hops >= 2 else 0
+    out = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev) if (hops == 2 and emit_h1) else None
+    ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev) if emit_ids else None
+    w1 = torch.empty((B, k1), dtype=torch.float32, device=dev) if emit_ids else None
+    ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev) if (emit_ids and hops == 2) else None
+    w2 = torch.empty((B, k1, k2), dtype=torch.float32, device=dev) if (emit_ids and hops == 2) else None
+    fan_host = (ctypes.c_int32 * max(1, hops))(*fan)
+    rc = lib().fsa_sample_wmean_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), _ptr(edge_weight), N,
+                                    _ptr(x), _x_dtype(x), D, _ptr(seeds), B,
+                                    ctypes.cast(fan_host, ctypes.c_void_p), hops, seed & (2**64 - 1),
+                                    _ptr(out), _ptr(out_h1), _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
+                                    _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_sample_wmean_fwd")
+    return out, out_h1, ids1, ids2, w1, w2
+
+
+def fsa_wmean_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, w1: torch.Tensor,
+                         ids2: Optional[torch.Tensor] = None, w2: Optional[torch.Tensor] = None, *,
+                         emit_h1: bool = True, stream: Optional[torch.cuda.Stream] = None):
+    """Weighted mean over saved IDs and weights.  Returns (out, out_h1)."""
+    _need(x, "x"); _need(ids1, "ids1", torch.int32); _need(w1, "w1", torch.float32)
+    B, k1 = ids1.shape
+    N, D = x.shape
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32); _need(w2, "w2", torch.float32)
+        k2 = ids2.shape[2]
+    out = torch.empty((B, D), dtype=x.dtype, device=x.device)
+    out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=x.device) if (ids2 is not None and emit_h1) else None
+    rc = lib().fsa_wmean_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
+                                    B, k1, k2, _ptr(out), _ptr(out_h1), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_wmean_replay_fwd")
+    return out, out_h1
+
+
+def fsa_wmean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, w1: torch.Tensor,
+                  ids2: Optional[torch.Tensor] = None, w2: Optional[torch.Tensor] = None,
+                  grad_h1: Optional[torch.Tensor] = None, *, grad_x: torch.Tensor,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Weighted backward: scatter-add into grad_x [N,D] fp32 (accumulated, not zeroed)."""
+    _need(grad_out, "grad_out", torch.float32); _need(ids1, "ids1", torch.int32); _need(w1, "w1", torch.float32)
+    _need(grad_x, "grad_x", torch.float32)
+    B, k1 = ids1.shape
+    D = grad_out.shape[1]
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32); _need(w2, "w2", torch.float32)
+        k2 = ids2.shape[2]
+    if grad_h1 is not None:
+        _need(grad_h1, "grad_h1", torch.float32)
+    rc = lib().fsa_wmean_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
+                             B, k1, k2, D, _ptr(grad_x), grad_x.shape[0], _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_wmean_bwd")
     return grad_x

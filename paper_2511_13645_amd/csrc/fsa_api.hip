@@ -117,6 +117,91 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
     return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
 }
 
+int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         const float* edge_weight, int64_t num_nodes,
+                         const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, int num_hops,
+                         uint64_t seed, void* out, void* out_h1,
+                         int32_t* out_ids1, int32_t* out_ids2, float* out_w1, float* out_w2,
+                         void* stream) {
+    if (!indptr || !indices || !edge_weight || !x || !fanouts) return FSA_ERR_NULL;
+    if (B != 0 && (!seeds || !out)) return FSA_ERR_NULL;
+    if (indptr_type != FSA_I32 && indptr_type != FSA_I64) return FSA_ERR_DTYPE;
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    if (num_hops != 1 && num_hops != 2) return FSA_ERR_ARG;
+    const int32_t k1 = fanouts[0];
+    const int32_t k2 = num_hops == 2 ? fanouts[1] : 0;
+    if (!fanout_ok(k1) || (num_hops == 2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (num_hops == 1 && (out_h1 || out_ids2 || out_w2)) return FSA_ERR_ARG;
+    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    if (!aligned(indptr, indptr_type == FSA_I64 ? 8 : 4) || !aligned(indices, 4) || !aligned(edge_weight, 4) ||
+        !aligned(seeds, 4) || !aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) ||
+        !aligned(out_ids1, 4) || !aligned(out_ids2, 4) || !aligned(out_w1, 4) || !aligned(out_w2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    const void* rows[3] = {x, out, out_h1};
+    fsa::FwdArgs a{};
+    a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
+    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.seeds = seeds; a.B = B; a.k1 = k1; a.k2 = k2; a.hops = num_hops; a.seed = seed;
+    a.out = out; a.out_h1 = out_h1; a.out_ids1 = out_ids1; a.out_ids2 = out_ids2;
+    a.geom = row_geometry(D, eb, rows, 3);
+    fsa::WeightArgs w{};
+    w.edge_w = edge_weight; w.out_w1 = out_w1; w.out_w2 = out_w2;
+    return fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2,
+                         const float* w1, const float* w2,
+                         int64_t B, int32_t k1, int32_t k2,
+                         void* out, void* out_h1, void* stream) {
+    if (!x) return FSA_ERR_NULL;
+    if (B != 0 && (!ids1 || !w1 || !out || (ids2 && !w2))) return FSA_ERR_NULL;
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && out_h1) return FSA_ERR_ARG;
+    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(ids1, 4) || !aligned(ids2, 4) ||
+        !aligned(w1, 4) || !aligned(w2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    const void* rows[3] = {x, out, out_h1};
+    fsa::FwdArgs a{};
+    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.hops = ids2 ? 2 : 1;
+    a.ids1 = ids1; a.ids2 = ids2; a.out = out; a.out_h1 = out_h1;
+    a.geom = row_geometry(D, eb, rows, 3);
+    fsa::WeightArgs w{};
+    w.w1 = w1; w.w2 = w2;
+    return fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_wmean_bwd(const float* grad_out, const float* grad_h1,
+                  const int32_t* ids1, const int32_t* ids2,
+                  const float* w1, const float* w2,
+                  int64_t B, int32_t k1, int32_t k2, int64_t D,
+                  float* grad_x, int64_t num_nodes, void* stream) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1 || !w1 || (ids2 && !w2))) return FSA_ERR_NULL;
+    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && grad_h1) return FSA_ERR_ARG;
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4) ||
+        !aligned(w1, 4) || !aligned(w2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    fsa::BwdArgs a{};
+    a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
+    fsa::WeightArgs w{};
+    w.w1 = w1; w.w2 = w2;
+    return fsa::launch_backward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
 const char* fsa_status_string(int status) {
     switch (status) {
         case FSA_OK:        return "ok";

@@ -138,6 +138,12 @@ template <int VB> struct Chunk<f32_t, VB> {
         else if constexpr (VB == 8) { acc[0] += bits_f32(r.x); acc[1] += bits_f32(r.y); }
         else { acc[0] += bits_f32(r); }
     }
+    // acc += w * row chunk (weighted mean)
+    static __device__ __forceinline__ void fma(float (&acc)[VE], const Raw& r, float w) {
+        if constexpr (VB == 16) { acc[0] = fmaf(w, bits_f32(r.x), acc[0]); acc[1] = fmaf(w, bits_f32(r.y), acc[1]); acc[2] = fmaf(w, bits_f32(r.z), acc[2]); acc[3] = fmaf(w, bits_f32(r.w), acc[3]); }
+        else if constexpr (VB == 8) { acc[0] = fmaf(w, bits_f32(r.x), acc[0]); acc[1] = fmaf(w, bits_f32(r.y), acc[1]); }
+        else { acc[0] = fmaf(w, bits_f32(r), acc[0]); }
+    }
     static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {
         Raw r;
         if constexpr (VB == 16) { r.x = __float_as_uint(v[0]); r.y = __float_as_uint(v[1]); r.z = __float_as_uint(v[2]); r.w = __float_as_uint(v[3]); }
@@ -159,6 +165,17 @@ template <int VB> struct Chunk<bf16_t, VB> {
         else if constexpr (VB == 8) { add2(acc[0], acc[1], r.x); add2(acc[2], acc[3], r.y); }
         else if constexpr (VB == 4) { add2(acc[0], acc[1], r); }
         else { acc[0] += bits_f32(((uint32_t)r) << 16); }
+    }
+    static __device__ __forceinline__ void fma2(float& lo, float& hi, uint32_t v, float w) {
+        lo = fmaf(w, bits_f32(v << 16), lo);
+        hi = fmaf(w, bits_f32(v & 0xffff0000u), hi);
+    }
+    // acc += w * row chunk (weighted mean)
+    static __device__ __forceinline__ void fma(float (&acc)[VE], const Raw& r, float w) {
+        if constexpr (VB == 16) { fma2(acc[0], acc[1], r.x, w); fma2(acc[2], acc[3], r.y, w); fma2(acc[4], acc[5], r.z, w); fma2(acc[6], acc[7], r.w, w); }
+        else if constexpr (VB == 8) { fma2(acc[0], acc[1], r.x, w); fma2(acc[2], acc[3], r.y, w); }
+        else if constexpr (VB == 4) { fma2(acc[0], acc[1], r, w); }
+        else { acc[0] = fmaf(w, bits_f32(((uint32_t)r) << 16), acc[0]); }
     }
     static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
         // fptrunc to bfloat16 is round-to-nearest-even; gfx950 does a pair per instruction

@@ -28,7 +28,17 @@ struct BwdArgs {
     int64_t B; int k1; int k2; int64_t D; float* grad_x;
 };
 
+// Weighted mean: the same launches with per-edge weights (edge_w aligned with indices) and
+// the sampled weights emitted / taken back next to the IDs.
+struct WeightArgs {
+    const float* edge_w;                        // sampling forward
+    const float* w1; const float* w2;           // replay / backward inputs
+    float* out_w1; float* out_w2;               // sampling forward outputs (nullable)
+};
+
 hipError_t launch_forward(const FwdArgs& a, hipStream_t stream);
+hipError_t launch_forward_weighted(const FwdArgs& a, const WeightArgs& w, hipStream_t stream);
+hipError_t launch_backward_weighted(const BwdArgs& a, const WeightArgs& w, hipStream_t stream);
 hipError_t launch_backward(const BwdArgs& a, hipStream_t stream);
 
 }  // namespace fsa

@@ -101,3 +101,33 @@ def test_binding_fails_loudly_without_library(fsa, monkeypatch):
     monkeypatch.setattr(fsa, "LIB_PATH", "/nonexistent/libfsa_hip.so")
     with pytest.raises(RuntimeError, match="HIP library missing"):
         fsa.lib()
+
+
+def test_weighted_entry_points_reject_bad_arguments(fsa):
+    L = fsa.lib()
+    fan = (ctypes.c_int32 * 2)(5, 3)
+    fp = ctypes.cast(fan, ctypes.c_void_p)
+
+    def fwd(**k):
+        a = dict(indptr=FAKE, itype=0, indices=FAKE, ew=FAKE, n=100, x=FAKE, xt=0, D=16, seeds=FAKE, B=8, fan=fp,
+                 hops=2, seed=1, out=FAKE, h1=FAKE, i1=FAKE, i2=FAKE, w1=FAKE, w2=FAKE, s=None)
+        a.update(k)
+        return L.fsa_sample_wmean_fwd(*[a[n] for n in ("indptr", "itype", "indices", "ew", "n", "x", "xt", "D", "seeds",
+                                                       "B", "fan", "hops", "seed", "out", "h1", "i1", "i2", "w1", "w2", "s")])
+    assert fwd(ew=None) == -1 and fwd(x=None) == -1 and fwd(out=None) == -1
+    assert fwd(hops=3) == -2 and fwd(D=0) == -2
+    assert fwd(hops=1, h1=None, i2=None) == -2        # 1-hop takes no hop-2 weight output either
+    assert fwd(ew=FAKE + 2) == -4 and fwd(w2=FAKE + 1) == -4
+    assert fwd(B=0) == 0
+
+    def rp(**k):
+        a = dict(x=FAKE, xt=0, D=8, n=10, ids1=FAKE, ids2=FAKE, w1=FAKE, w2=FAKE, B=4, k1=3, k2=2, out=FAKE, h1=FAKE, s=None)
+        a.update(k)
+        return L.fsa_wmean_replay_fwd(*[a[n] for n in ("x", "xt", "D", "n", "ids1", "ids2", "w1", "w2", "B", "k1", "k2", "out", "h1", "s")])
+    assert rp(w1=None) == -1 and rp(w2=None) == -1 and rp(k1=65) == -2 and rp(w1=FAKE + 2) == -4 and rp(B=0) == 0
+
+    def bw(**k):
+        a = dict(go=FAKE, gh=FAKE, ids1=FAKE, ids2=FAKE, w1=FAKE, w2=FAKE, B=4, k1=3, k2=2, D=8, gx=FAKE, n=10, s=None)
+        a.update(k)
+        return L.fsa_wmean_bwd(*[a[n] for n in ("go", "gh", "ids1", "ids2", "w1", "w2", "B", "k1", "k2", "D", "gx", "n", "s")])
+    assert bw(gx=None) == -1 and bw(w1=None) == -1 and bw(ids2=None, w2=None, gh=FAKE) == -2 and bw(B=0) == 0
