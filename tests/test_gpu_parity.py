@@ -251,3 +251,20 @@ def test_backward_with_heavily_shared_rows(fsa, orc, n_targets, B):
     seeds = rng.integers(0, n, B).astype(np.int32)
     run_case(fsa, orc, indptr, indices, x, seeds, [k], 3, what="shared rows %d" % n_targets)
     run_case(fsa, orc, indptr, indices, x, seeds[:777], [5, 4], 3, what="shared rows 2-hop %d" % n_targets)
+
+
+def test_very_wide_rows_and_large_batch(fsa, orc):
+    """Rows of 8192 floats (32 tiles per row) and a batch beyond 65,535 workgroups."""
+    rng = np.random.default_rng(8)
+    n = 600
+    indptr, indices = ragged_graph(n, seed=8, max_deg=40, hub_deg=300)
+    x = torch.from_numpy(rng.standard_normal((n, 8192)).astype(np.float32))
+    seeds = rng.integers(0, n, 33).astype(np.int32)
+    run_case(fsa, orc, indptr, indices, x, seeds, [6, 5], 1, what="D=8192 2-hop")
+    run_case(fsa, orc, indptr, indices, x, seeds, [9], 1, what="D=8192 1-hop")
+    n = 5000
+    indptr, indices = ragged_graph(n, seed=9, max_deg=30, hub_deg=500)
+    x = torch.from_numpy(rng.standard_normal((n, 16)).astype(np.float32))
+    seeds = rng.integers(0, n, 70_001).astype(np.int32)
+    run_case(fsa, orc, indptr, indices, x, seeds, [4, 3], 2, what="B=70001 2-hop")
+    run_case(fsa, orc, indptr, indices, x, seeds, [5], 2, what="B=70001 1-hop")
