@@ -91,6 +91,8 @@ def main() -> int:
     ap.add_argument("--cache", default="", help="directory with raw copies of the workload: written if "
                     "absent, loaded if present (counter runs use it: rocprofv3 --pmc does not survive the "
                     "in-process generation of the full-size graph on this image)")
+    ap.add_argument("--paths", action="store_true",
+                    help="also time the replay forward and (fp32 tables) the backward on the same batches")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
     args = ap.parse_args()
@@ -212,14 +214,73 @@ def main() -> int:
         except Exception:
             traffic = None
 
+    other_paths = None
+    if args.paths and emit:
+        # replay forward and backward on the IDs the timed launches emitted (one launch per batch)
+        other_paths = {}
+        n_p = min(steps, 50)
+        replay = L.fsa_mean_replay_fwd
+        x_code = binding.FSA_BF16 if x.dtype == torch.bfloat16 else binding.FSA_F32
+
+        def run_replay(i):
+            rc = replay(x.data_ptr(), x_code, D, N, id1_ptrs[i], id2_ptrs[i], B, k1, k2, out.data_ptr(),
+                        None if out_h1 is None else out_h1.data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError("fsa_mean_replay_fwd -> %d" % rc)
+        for i in range(warmup, warmup + 3):
+            run_replay(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(warmup, warmup + n_p):
+            run_replay(i)
+        e1.record()
+        torch.cuda.synchronize()
+        r_ms = e0.elapsed_time(e1) / n_p
+        rows_p = leaf_rows / steps
+        r_alg = rows_p * (D * elem + 4) + B * D * elem + (B * k1 * D * elem + 4 * B * k1 if hops == 2 else 0)
+        other_paths["replay_forward"] = {"launch_us": r_ms * 1e3, "rows_per_s": rows_p / (r_ms * 1e-3),
+                                         "hbm_gbps": r_alg / (r_ms * 1e-3) / 1e9,
+                                         "frac": r_alg / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        if x.dtype == torch.float32:
+            g_out = synth.upstream_grad((B, D), seed=3, device=dev)
+            g_h1 = synth.upstream_grad((B, k1, D), seed=4, device=dev) if hops == 2 else None
+            grad_x = torch.zeros((N, D), dtype=torch.float32, device=dev)
+            bwd = L.fsa_mean_bwd
+
+            def run_bwd(i):
+                rc = bwd(g_out.data_ptr(), None if g_h1 is None else g_h1.data_ptr(), id1_ptrs[i], id2_ptrs[i],
+                         B, k1, k2, D, grad_x.data_ptr(), N, stream)
+                if rc != 0:
+                    raise RuntimeError("fsa_mean_bwd -> %d" % rc)
+            for i in range(warmup, warmup + 2):
+                run_bwd(i)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(warmup, warmup + n_p):
+                run_bwd(i)                          # accumulates on; zero-filling grad_x is the caller's
+            e1.record()
+            torch.cuda.synchronize()
+            b_ms = e0.elapsed_time(e1) / n_p
+            payload = rows_p * D * 4                # bytes added into grad_x by atomics
+            b_alg = 2 * payload + 4 * rows_p + B * D * 4 + (B * k1 * D * 4 if hops == 2 else 0)
+            other_paths["backward"] = {"launch_us": b_ms * 1e3, "rows_per_s": rows_p / (b_ms * 1e-3),
+                                       "atomic_payload_gbps": payload / (b_ms * 1e-3) / 1e9,
+                                       "hbm_gbps": b_alg / (b_ms * 1e-3) / 1e9,
+                                       "frac": b_alg / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            del g_out, g_h1, grad_x
+        log("[bench] other paths: %s" % json.dumps(other_paths))
+
     saturated = None
-    if args.saturated_batch > 0 and hops == 2:
+    if args.saturated_batch > 0:
         Bs, n_sat = args.saturated_batch, 20
         s_seeds = synth.seed_batches(N, Bs, n_sat + 2, seed=5).to(dev)
         s_out = torch.empty((Bs, D), dtype=x.dtype, device=dev)
         s_h1 = torch.empty((Bs, k1, D), dtype=x.dtype, device=dev) if emit else None
         s_i1 = torch.empty((Bs, k1), dtype=torch.int32, device=dev) if emit else None
-        s_i2 = torch.empty((Bs, k1, k2), dtype=torch.int32, device=dev) if emit else None
+        s_i2 = torch.empty((Bs, k1, k2), dtype=torch.int32, device=dev) if (emit and hops == 2) else None
+        if hops == 1:
+            s_h1 = None
         tail = (Bs, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed, s_out.data_ptr(),
                 None if s_h1 is None else s_h1.data_ptr(), None if s_i1 is None else s_i1.data_ptr(),
                 None if s_i2 is None else s_i2.data_ptr(), stream)
@@ -234,8 +295,12 @@ def main() -> int:
         torch.cuda.synchronize()
         s_ms = e0.elapsed_time(e1) / n_sat
         o, h, i1, i2 = binding.fsa_sample_mean_fwd(g.indptr, g.indices, x, s_seeds[2], fan, w.sampler_seed, emit_h1=False)
-        s_leaf, s_hop1 = int((i2 >= 0).sum().item()), int((i1 >= 0).sum().item())
-        s_alg = algorithmic_bytes(s_leaf, s_hop1, Bs, k1, k2, D, elem, iptr, emit, emit)
+        if hops == 2:
+            s_leaf, s_hop1 = int((i2 >= 0).sum().item()), int((i1 >= 0).sum().item())
+            s_alg = algorithmic_bytes(s_leaf, s_hop1, Bs, k1, k2, D, elem, iptr, emit, emit)
+        else:
+            s_leaf = int((i1 >= 0).sum().item())
+            s_alg = s_leaf * (D * elem + 4) + Bs * (2 * iptr + 4 + D * elem) + (4 * Bs * k1 if emit else 0)
         saturated = {"global_batch": Bs, "launch_us": s_ms * 1e3, "rows_per_s": s_leaf / (s_ms * 1e-3),
                      "hbm_gbps": s_alg / (s_ms * 1e-3) / 1e9, "frac": s_alg / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         del s_seeds, s_out, s_h1, s_i1, s_i2
@@ -284,6 +349,7 @@ def main() -> int:
                      "kernel": "fwd2_kernel" if hops == 2 else "fwd1_kernel", "launch_us": kern_ms * 1e3},
         "cpu_baseline": cpu,
         "saturated": saturated,
+        "other_paths": other_paths,
     }
     print(json.dumps(line), flush=True)
     return 0
