@@ -93,6 +93,10 @@ def main() -> int:
                     "in-process generation of the full-size graph on this image)")
     ap.add_argument("--paths", action="store_true",
                     help="also time the replay forward and (fp32 tables) the backward on the same batches")
+    ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: time the forward at each, "
+                    "with and without ID / per-slot emission, on the same graph")
+    ap.add_argument("--feature-dtype", default="", choices=["", "f32", "bf16"],
+                    help="convert the workload's feature table to this type first (fp32 variant of the headline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
     args = ap.parse_args()
@@ -122,6 +126,9 @@ def main() -> int:
     t0 = time.time()
     w = load_or_make_workload(args.workload, args.scale, args.cache, dev)
     torch.cuda.synchronize()
+    want = {"": None, "f32": torch.float32, "bf16": torch.bfloat16}[args.feature_dtype]
+    if want is not None and w.x.dtype != want:
+        w.x = w.x.to(want)
     g, x = w.graph, w.x
     B = args.batch or w.batch
     fan = list(w.fanouts)
@@ -208,7 +215,8 @@ def main() -> int:
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % w.name)
-    if os.path.exists(tpath):
+    # the committed counter runs cover the workload as named (its own batch, table type, emission on)
+    if os.path.exists(tpath) and not args.batch and not args.feature_dtype and emit and args.scale == 1.0:
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
@@ -271,41 +279,49 @@ def main() -> int:
             del g_out, g_h1, grad_x
         log("[bench] other paths: %s" % json.dumps(other_paths))
 
-    saturated = None
-    if args.saturated_batch > 0:
-        Bs, n_sat = args.saturated_batch, 20
-        s_seeds = synth.seed_batches(N, Bs, n_sat + 2, seed=5).to(dev)
+    def forward_at_batch(Bs, emit_s, n_launch=20):
+        """Time `n_launch` back-to-back forward launches at batch size Bs on the same graph."""
+        if Bs > N:                               # seeds are drawn without replacement
+            log("[bench] B=%d exceeds the graph's %d nodes: skipped" % (Bs, N))
+            return None
+        s_seeds = synth.seed_batches(N, Bs, n_launch + 2, seed=5).to(dev)
         s_out = torch.empty((Bs, D), dtype=x.dtype, device=dev)
-        s_h1 = torch.empty((Bs, k1, D), dtype=x.dtype, device=dev) if emit else None
-        s_i1 = torch.empty((Bs, k1), dtype=torch.int32, device=dev) if emit else None
-        s_i2 = torch.empty((Bs, k1, k2), dtype=torch.int32, device=dev) if (emit and hops == 2) else None
-        if hops == 1:
-            s_h1 = None
+        s_h1 = torch.empty((Bs, k1, D), dtype=x.dtype, device=dev) if (emit_s and hops == 2) else None
+        s_i1 = torch.empty((Bs, k1), dtype=torch.int32, device=dev) if emit_s else None
+        s_i2 = torch.empty((Bs, k1, k2), dtype=torch.int32, device=dev) if (emit_s and hops == 2) else None
         tail = (Bs, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed, s_out.data_ptr(),
                 None if s_h1 is None else s_h1.data_ptr(), None if s_i1 is None else s_i1.data_ptr(),
                 None if s_i2 is None else s_i2.data_ptr(), stream)
         for i in range(2):
-            fwd(*fixed_head, s_seeds[i].data_ptr(), *tail)
+            rc = fwd(*fixed_head, s_seeds[i].data_ptr(), *tail)
+            if rc != 0:
+                raise RuntimeError("fsa_sample_mean_fwd -> %d" % rc)
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        for i in range(2, n_sat + 2):
+        for i in range(2, n_launch + 2):
             fwd(*fixed_head, s_seeds[i].data_ptr(), *tail)
         e1.record()
         torch.cuda.synchronize()
-        s_ms = e0.elapsed_time(e1) / n_sat
+        s_ms = e0.elapsed_time(e1) / n_launch
+        # rows of one of the timed batches, counted by an untimed emitting launch
         o, h, i1, i2 = binding.fsa_sample_mean_fwd(g.indptr, g.indices, x, s_seeds[2], fan, w.sampler_seed, emit_h1=False)
         if hops == 2:
             s_leaf, s_hop1 = int((i2 >= 0).sum().item()), int((i1 >= 0).sum().item())
-            s_alg = algorithmic_bytes(s_leaf, s_hop1, Bs, k1, k2, D, elem, iptr, emit, emit)
+            s_alg = algorithmic_bytes(s_leaf, s_hop1, Bs, k1, k2, D, elem, iptr, emit_s, emit_s)
         else:
             s_leaf = int((i1 >= 0).sum().item())
-            s_alg = s_leaf * (D * elem + 4) + Bs * (2 * iptr + 4 + D * elem) + (4 * Bs * k1 if emit else 0)
-        saturated = {"global_batch": Bs, "launch_us": s_ms * 1e3, "rows_per_s": s_leaf / (s_ms * 1e-3),
-                     "hbm_gbps": s_alg / (s_ms * 1e-3) / 1e9, "frac": s_alg / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
-        del s_seeds, s_out, s_h1, s_i1, s_i2
-        log("[bench] B=%d: %.1f us/launch, %.2f G rows/s, %.0f GB/s algorithmic" %
-            (Bs, s_ms * 1e3, saturated["rows_per_s"] / 1e9, saturated["hbm_gbps"]))
+            s_alg = s_leaf * (D * elem + 4) + Bs * (2 * iptr + 4 + D * elem) + (4 * Bs * k1 if emit_s else 0)
+        r = {"global_batch": Bs, "emit": emit_s, "launch_us": s_ms * 1e3, "rows_per_s": s_leaf / (s_ms * 1e-3),
+             "hbm_gbps": s_alg / (s_ms * 1e-3) / 1e9, "frac": s_alg / (s_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        log("[bench] B=%d emit=%s: %.1f us/launch, %.2f G rows/s, %.0f GB/s algorithmic (%.3f)" %
+            (Bs, emit_s, s_ms * 1e3, r["rows_per_s"] / 1e9, r["hbm_gbps"], r["frac"]))
+        return r
+
+    saturated = forward_at_batch(args.saturated_batch, emit) if args.saturated_batch > 0 else None
+    batch_sweep = None
+    if args.batch_sweep:
+        batch_sweep = [forward_at_batch(int(b), e) for b in args.batch_sweep.split(",") for e in (True, False)]
 
     cpu = None
     if args.cpu_seconds > 0:
@@ -350,6 +366,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "saturated": saturated,
         "other_paths": other_paths,
+        "batch_sweep": batch_sweep,
     }
     print(json.dumps(line), flush=True)
     return 0

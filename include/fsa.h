@@ -23,8 +23,8 @@
  *     when ids1[b,j] is -1;
  *   - in the 2-hop mean a hop-1 node with an empty row leaves both the sum and the divisor;
  *     a seed with nothing to average gets a zero row (never NaN);
- *   - sums are accumulated in fp32 in a fixed order; outputs have the feature type (bf16
- *     outputs are rounded to nearest even from the fp32 result).
+ *   - sums are accumulated in fp32 in a fixed order; outputs have the feature type (bf16 and
+ *     fp16 outputs are rounded to nearest even from the fp32 result).
  * Because every draw is keyed by (seed, node, hop, step) the sampled IDs do not depend on
  * batch size, batch order, launch shape or how seeds are split over devices.
  *
@@ -49,7 +49,9 @@
 extern "C" {
 #endif
 
-typedef enum { FSA_F32 = 0, FSA_BF16 = 1 } fsa_dtype;   /* feature / output element type */
+/* element types: fp32, bfloat16, IEEE half.  The paper's kernels are FP32-only and name that
+ * as a limitation (Sec. 5 "Limitations"); the 16-bit types are this library's extension. */
+typedef enum { FSA_F32 = 0, FSA_BF16 = 1, FSA_F16 = 2 } fsa_dtype;
 typedef enum { FSA_I32 = 0, FSA_I64 = 1 } fsa_itype;    /* indptr element type           */
 
 typedef enum {
@@ -112,6 +114,30 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
                  const int32_t* ids1, const int32_t* ids2,
                  int64_t B, int32_t k1, int32_t k2, int64_t D,
                  float* grad_x, int64_t num_nodes, void* stream);
+
+/*
+ * Reduced-precision backward (the paper lists FP32-only kernels as a limitation, Sec. 5
+ * "Limitations"; this entry point lifts it).  Same operation as fsa_mean_bwd with
+ *   grad_out / grad_h1 of type grad_dtype  (FSA_F32, FSA_BF16 or FSA_F16), and
+ *   grad_x of type grad_x_dtype:
+ *     FSA_F32             an fp32 master gradient: 16-bit upstream gradients are widened
+ *                         exactly, all arithmetic and the atomics are fp32;
+ *     FSA_BF16 / FSA_F16  grad_x in the 16-bit type; grad_dtype must be the same type or
+ *                         FSA_F32.  Each contribution is formed in fp32, rounded once to the
+ *                         16-bit type (nearest even) and added with packed two-element
+ *                         hardware atomics, each of which rounds the running sum again: with
+ *                         n additions into an element the error is bounded by about
+ *                         (n + 1) * 2^-8 (bf16) or (n + 1) * 2^-10 (fp16) times the sum of
+ *                         the absolute contributions, whatever way the atomic unit rounds.
+ *                         fp16 sums can overflow to infinity.
+ * With any 16-bit operand D must be even (FSA_ERR_ARG otherwise) and the arrays 4-byte
+ * aligned: lanes read and add element pairs.  grad_dtype == grad_x_dtype == FSA_F32 is
+ * exactly fsa_mean_bwd.  grad_x is accumulated into; the order of additions varies.
+ */
+int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
+                    const int32_t* ids1, const int32_t* ids2,
+                    int64_t B, int32_t k1, int32_t k2, int64_t D,
+                    void* grad_x, int grad_x_dtype, int64_t num_nodes, void* stream);
 
 /*
  * Weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted numerators

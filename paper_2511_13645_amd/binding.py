@@ -16,12 +16,12 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfsa_hip.so")
 
-FSA_F32, FSA_BF16 = 0, 1
+FSA_F32, FSA_BF16, FSA_F16 = 0, 1, 2
 FSA_I32, FSA_I64 = 0, 1
 FSA_OK = 0
 FSA_KMAX = 64
 
-EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_status_string",
+EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_mean_bwd_lp", "fsa_status_string",
            "fsa_sample_wmean_fwd", "fsa_wmean_replay_fwd", "fsa_wmean_bwd")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -48,6 +48,8 @@ def lib() -> ctypes.CDLL:
         L.fsa_mean_replay_fwd.restype = ci
         L.fsa_mean_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
         L.fsa_mean_bwd.restype = ci
+        L.fsa_mean_bwd_lp.argtypes = [vp, vp, ci, vp, vp, i64, i32, i32, i64, vp, ci, i64, vp]
+        L.fsa_mean_bwd_lp.restype = ci
         L.fsa_sample_wmean_fwd.argtypes = [vp, ci, vp, vp, i64, vp, ci, i64, vp, i64, vp, ci, u64,
                                            vp, vp, vp, vp, vp, vp, vp]
         L.fsa_sample_wmean_fwd.restype = ci
@@ -74,7 +76,9 @@ def _x_dtype(x: torch.Tensor) -> int:
         return FSA_F32
     if x.dtype == torch.bfloat16:
         return FSA_BF16
-    raise TypeError("features must be float32 or bfloat16, got %s" % x.dtype)
+    if x.dtype == torch.float16:
+        return FSA_F16
+    raise TypeError("expected float32, bfloat16 or float16, got %s" % x.dtype)
 
 
 def _indptr_type(indptr: torch.Tensor) -> int:
@@ -187,6 +191,32 @@ def fsa_mean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torc
                             _ptr(grad_x), N, _stream(stream))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd")
+    return grad_x
+
+
+def fsa_mean_bwd_lp(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torch.Tensor] = None,
+                    grad_h1: Optional[torch.Tensor] = None, *, grad_x: torch.Tensor,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Reduced-precision backward: grad_out / grad_h1 in fp32, bf16 or fp16; grad_x [N,D] either an
+    fp32 master gradient or a 16-bit table added to with packed atomics (accumulated, not zeroed)."""
+    _need(grad_out, "grad_out"); _need(ids1, "ids1", torch.int32); _need(grad_x, "grad_x")
+    B, k1 = ids1.shape
+    D = grad_out.shape[1]
+    N = grad_x.shape[0]
+    if grad_x.shape[1] != D or grad_out.shape[0] != B:
+        raise ValueError("shape mismatch between grad_out, ids1 and grad_x")
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32)
+        k2 = ids2.shape[2]
+    if grad_h1 is not None:
+        _need(grad_h1, "grad_h1", grad_out.dtype)
+        if tuple(grad_h1.shape) != (B, k1, D):
+            raise ValueError("grad_h1 must be [B,k1,D]")
+    rc = lib().fsa_mean_bwd_lp(_ptr(grad_out), _ptr(grad_h1), _x_dtype(grad_out), _ptr(ids1), _ptr(ids2),
+                               B, k1, k2, D, _ptr(grad_x), _x_dtype(grad_x), N, _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean_bwd_lp")
     return grad_x
 
 

@@ -29,11 +29,13 @@ fsa::RowGeom row_geometry(int64_t D, int elem_bytes, const void* const* row_ptrs
 }
 
 int check_common(int x_dtype, int64_t D, int64_t num_nodes, int64_t B) {
-    if (x_dtype != FSA_F32 && x_dtype != FSA_BF16) return FSA_ERR_DTYPE;
+    if (x_dtype != FSA_F32 && x_dtype != FSA_BF16 && x_dtype != FSA_F16) return FSA_ERR_DTYPE;
     if (D <= 0 || D > (int64_t)1 << 24 || num_nodes <= 0 || num_nodes > (int64_t)INT32_MAX) return FSA_ERR_ARG;
     if (B < 0 || B > (int64_t)INT32_MAX) return FSA_ERR_ARG;
     return FSA_OK;
 }
+
+int elem_bytes(int dtype) { return dtype == FSA_F32 ? 4 : 2; }
 
 bool fanout_ok(int32_t k) { return k >= 1 && k <= FSA_KMAX; }
 
@@ -55,7 +57,7 @@ int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indi
     const int32_t k2 = num_hops == 2 ? fanouts[1] : 0;
     if (!fanout_ok(k1) || (num_hops == 2 && !fanout_ok(k2))) return FSA_ERR_ARG;
     if (num_hops == 1 && (out_h1 || out_ids2)) return FSA_ERR_ARG;
-    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    const int eb = elem_bytes(x_dtype);
     if (!aligned(indptr, indptr_type == FSA_I64 ? 8 : 4) || !aligned(indices, 4) || !aligned(seeds, 4) ||
         !aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) ||
         !aligned(out_ids1, 4) || !aligned(out_ids2, 4))
@@ -65,7 +67,7 @@ int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indi
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
     a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
-    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.x = x; a.x_kind = x_dtype; a.D = D;
     a.seeds = seeds; a.B = B; a.k1 = k1; a.k2 = k2; a.hops = num_hops; a.seed = seed;
     a.ids1 = nullptr; a.ids2 = nullptr;
     a.out = out; a.out_h1 = out_h1; a.out_ids1 = out_ids1; a.out_ids2 = out_ids2;
@@ -82,7 +84,7 @@ int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes
     if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
     if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
     if (!ids2 && out_h1) return FSA_ERR_ARG;
-    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    const int eb = elem_bytes(x_dtype);
     if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(ids1, 4) || !aligned(ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
@@ -90,7 +92,7 @@ int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
     a.indptr = nullptr; a.indices = nullptr; a.seeds = nullptr;
-    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.x = x; a.x_kind = x_dtype; a.D = D;
     a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.hops = ids2 ? 2 : 1; a.seed = 0;
     a.ids1 = ids1; a.ids2 = ids2;
     a.out = out; a.out_h1 = out_h1; a.out_ids1 = nullptr; a.out_ids2 = nullptr;
@@ -117,6 +119,32 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
     return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
 }
 
+int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
+                    const int32_t* ids1, const int32_t* ids2,
+                    int64_t B, int32_t k1, int32_t k2, int64_t D,
+                    void* grad_x, int grad_x_dtype, int64_t num_nodes, void* stream) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1)) return FSA_ERR_NULL;
+    if (int rc = check_common(grad_dtype, D, num_nodes, B)) return rc;
+    if (int rc = check_common(grad_x_dtype, D, num_nodes, B)) return rc;
+    // a 16-bit grad_x takes gradients of its own type or fp32
+    if (grad_x_dtype != FSA_F32 && grad_dtype != FSA_F32 && grad_dtype != grad_x_dtype) return FSA_ERR_DTYPE;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && grad_h1) return FSA_ERR_ARG;
+    const bool pairs = grad_dtype != FSA_F32 || grad_x_dtype != FSA_F32;
+    if (pairs && (D & 1)) return FSA_ERR_ARG;                  // lanes own element pairs
+    // 16-bit arrays are accessed a pair (4 bytes) at a time
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+
+    fsa::BwdArgs a{};
+    a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
+    a.grad_kind = grad_dtype; a.grad_x_kind = grad_x_dtype;
+    return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
 int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
                          const float* edge_weight, int64_t num_nodes,
                          const void* x, int x_dtype, int64_t D,
@@ -133,7 +161,7 @@ int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
     const int32_t k2 = num_hops == 2 ? fanouts[1] : 0;
     if (!fanout_ok(k1) || (num_hops == 2 && !fanout_ok(k2))) return FSA_ERR_ARG;
     if (num_hops == 1 && (out_h1 || out_ids2 || out_w2)) return FSA_ERR_ARG;
-    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    const int eb = elem_bytes(x_dtype);
     if (!aligned(indptr, indptr_type == FSA_I64 ? 8 : 4) || !aligned(indices, 4) || !aligned(edge_weight, 4) ||
         !aligned(seeds, 4) || !aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) ||
         !aligned(out_ids1, 4) || !aligned(out_ids2, 4) || !aligned(out_w1, 4) || !aligned(out_w2, 4))
@@ -143,7 +171,7 @@ int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
     a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
-    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.x = x; a.x_kind = x_dtype; a.D = D;
     a.seeds = seeds; a.B = B; a.k1 = k1; a.k2 = k2; a.hops = num_hops; a.seed = seed;
     a.out = out; a.out_h1 = out_h1; a.out_ids1 = out_ids1; a.out_ids2 = out_ids2;
     a.geom = row_geometry(D, eb, rows, 3);
@@ -162,7 +190,7 @@ int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
     if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
     if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
     if (!ids2 && out_h1) return FSA_ERR_ARG;
-    const int eb = x_dtype == FSA_BF16 ? 2 : 4;
+    const int eb = elem_bytes(x_dtype);
     if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(ids1, 4) || !aligned(ids2, 4) ||
         !aligned(w1, 4) || !aligned(w2, 4))
         return FSA_ERR_ALIGN;
@@ -170,7 +198,7 @@ int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
 
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
-    a.x = x; a.x_is_bf16 = x_dtype == FSA_BF16; a.D = D;
+    a.x = x; a.x_kind = x_dtype; a.D = D;
     a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.hops = ids2 ? 2 : 1;
     a.ids1 = ids1; a.ids2 = ids2; a.out = out; a.out_h1 = out_h1;
     a.geom = row_geometry(D, eb, rows, 3);

@@ -12,16 +12,78 @@
 #include "fsa_internal.h"
 
 #include <cstdlib>
+#include <type_traits>
 
 namespace fsa {
 
 struct BwdParams {
-    const float* grad_out; const float* grad_h1; const int32_t* ids1; const int32_t* ids2;
-    float* grad_x; int64_t B; int64_t D; int k1, k2;
+    const void* grad_out; const void* grad_h1; const int32_t* ids1; const int32_t* ids2;
+    void* grad_x; int64_t B; int64_t D; int k1, k2;
 };
 
-__device__ __forceinline__ void atomic_add_f32(float* addr, float v) {
-    unsafeAtomicAdd(addr, v);        // global_atomic_add_f32, no return value
+// ---------------------------------------------------------------------------------------
+// Element types of the incoming gradients (GT) and of grad_x (XG).  With fp32 on both sides a
+// lane owns one element of the row (EPL = 1) and adds it with global_atomic_add_f32.  As soon
+// as one side is 16-bit a lane owns two consecutive elements (EPL = 2; D is even): 16-bit
+// gradients are read a pair per 4-byte load, and a 16-bit grad_x takes the pair in ONE packed
+// atomic (global_atomic_pk_add_bf16 / _f16), which halves the number of atomic operations per
+// row -- the L2 atomic unit, not bandwidth, bounds this kernel.  Products and sums before the
+// atomic are fp32; the value is rounded to the 16-bit type once (nearest-even) and every
+// packed atomic rounds the running sum again.
+// ---------------------------------------------------------------------------------------
+struct g_f32 { using T = float; };
+struct g_bf16 { using T = uint16_t; };
+struct g_f16 { using T = uint16_t; };
+
+template <typename GT, typename XG> struct Epl { static constexpr int value = 2; };
+template <> struct Epl<g_f32, g_f32> { static constexpr int value = 1; };
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+
+// EPL consecutive gradient elements starting at element index `idx` (even when EPL == 2).
+template <typename GT, int EPL>
+__device__ __forceinline__ void load_grad(const void* base, int64_t idx, float (&g)[EPL]) {
+    if constexpr (std::is_same<GT, g_f32>::value) {
+        const float* p = static_cast<const float*>(base) + idx;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) g[e] = p[e];
+    } else {
+        static_assert(EPL == 2, "16-bit gradients are read in pairs");
+        const uint32_t w = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(base) + idx);
+        if constexpr (std::is_same<GT, g_bf16>::value) {
+            g[0] = __uint_as_float(w << 16);
+            g[1] = __uint_as_float(w & 0xffff0000u);
+        } else {
+            f16x2_t h;
+            __builtin_memcpy(&h, &w, sizeof h);
+            const f32x2_t f = __builtin_convertvector(h, f32x2_t);
+            g[0] = f[0];
+            g[1] = f[1];
+        }
+    }
+}
+
+// grad_x[idx .. idx+EPL) += v, by hardware atomics without a return value.
+template <typename XG, int EPL>
+__device__ __forceinline__ void atomic_add_row(void* base, int64_t idx, const float (&v)[EPL]) {
+    if constexpr (std::is_same<XG, g_f32>::value) {
+        float* p = static_cast<float*>(base) + idx;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) unsafeAtomicAdd(p + e, v[e]);          // global_atomic_add_f32
+    } else {
+        static_assert(EPL == 2, "16-bit grad_x takes packed pairs");
+        const f32x2_t f = {v[0], v[1]};
+        uint16_t* p = static_cast<uint16_t*>(base) + idx;
+        if constexpr (std::is_same<XG, g_bf16>::value) {
+            const bf16x2_t b = __builtin_convertvector(f, bf16x2_t);
+            __builtin_amdgcn_global_atomic_fadd_v2bf16(reinterpret_cast<bf16x2_t*>(p), b);
+        } else {
+            const f16x2_t h = __builtin_convertvector(f, f16x2_t);
+            __builtin_amdgcn_global_atomic_fadd_v2f16(reinterpret_cast<f16x2_t*>(p), h);
+        }
+    }
 }
 
 // Merge equal IDs inside a segment of `k` lanes starting at seg_base.  Returns how many
@@ -65,7 +127,9 @@ __device__ __forceinline__ int hot_hash(int id) {
     return (int)(((uint32_t)id * 2654435761u) >> 21);              // 11 bits -> kHotBuckets
 }
 
+template <typename GT, typename XG>
 __global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p, int spw, int hot_rows) {
+    constexpr int EPL = Epl<GT, XG>::value;
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -155,14 +219,23 @@ __global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p, int spw, i
             hot_of[slot] = hr;
         }
         __builtin_amdgcn_wave_barrier();
-        for (int64_t d0 = 0; d0 < p.D; d0 += kWave) {
-            const int64_t d = d0 + lane;
+        for (int64_t d0 = 0; d0 < p.D; d0 += kWave * EPL) {
+            const int64_t d = d0 + lane * EPL;
             if (d < p.D) {
-                const float g = p.grad_out[b * p.D + d];
+                float g[EPL];
+                load_grad<GT, EPL>(p.grad_out, b * p.D + d, g);
                 for (int e = 0; e < n; ++e) {
                     const int hr = hot_of[e];
-                    if (hr >= 0) atomicAdd(&hot[(int64_t)hr * p.D + d], g * weight[e]);
-                    else atomic_add_f32(p.grad_x + (int64_t)rows[e] * p.D + d, g * weight[e]);
+                    const float wt = weight[e];
+                    float v[EPL];
+#pragma unroll
+                    for (int c = 0; c < EPL; ++c) v[c] = g[c] * wt;
+                    if (hr >= 0) {
+#pragma unroll
+                        for (int c = 0; c < EPL; ++c) atomicAdd(&hot[(int64_t)hr * p.D + d + c], v[c]);
+                    } else {
+                        atomic_add_row<XG, EPL>(p.grad_x, (int64_t)rows[e] * p.D + d, v);
+                    }
                 }
             }
         }
@@ -173,13 +246,19 @@ __global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p, int spw, i
         __syncthreads();
         const int n_rows = flags[1];
         for (int r = wave; r < n_rows; r += nw) {
-            float* dst = p.grad_x + (int64_t)row_node[r] * p.D;
-            for (int64_t d = lane; d < p.D; d += kWave) atomic_add_f32(dst + d, hot[(int64_t)r * p.D + d]);
+            for (int64_t d = (int64_t)lane * EPL; d < p.D; d += kWave * EPL) {
+                float v[EPL];
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) v[c] = hot[(int64_t)r * p.D + d + c];
+                atomic_add_row<XG, EPL>(p.grad_x, (int64_t)row_node[r] * p.D + d, v);
+            }
         }
     }
 }
 
+template <typename GT, typename XG>
 __global__ __launch_bounds__(512) void bwd2_kernel(const BwdParams p) {
+    constexpr int EPL = Epl<GT, XG>::value;
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -239,15 +318,28 @@ __global__ __launch_bounds__(512) void bwd2_kernel(const BwdParams p) {
         const int n = uniq[q];
         const int64_t j = wave + q * nw;
         const float fc = (float)c;
-        for (int64_t d0 = 0; d0 < p.D; d0 += kWave) {
-            const int64_t d = d0 + lane;
+        for (int64_t d0 = 0; d0 < p.D; d0 += kWave * EPL) {
+            const int64_t d = d0 + lane * EPL;
             if (d < p.D) {
-                float gsum = p.grad_out[b * p.D + d] / fc1;
-                if (p.grad_h1) gsum += p.grad_h1[(b * k1 + j) * p.D + d];
-                gsum = gsum / fc;
-                for (int e = 0; e < n; ++e)
-                    atomic_add_f32(p.grad_x + (int64_t)leaf[q * k2 + e] * p.D + d,
-                                   gsum * (float)mul[q * k2 + e]);
+                float gsum[EPL];
+                load_grad<GT, EPL>(p.grad_out, b * p.D + d, gsum);
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) gsum[c] = gsum[c] / fc1;
+                if (p.grad_h1) {
+                    float gh[EPL];
+                    load_grad<GT, EPL>(p.grad_h1, (b * k1 + j) * p.D + d, gh);
+#pragma unroll
+                    for (int c = 0; c < EPL; ++c) gsum[c] += gh[c];
+                }
+#pragma unroll
+                for (int c = 0; c < EPL; ++c) gsum[c] = gsum[c] / fc;
+                for (int e = 0; e < n; ++e) {
+                    const float m = (float)mul[q * k2 + e];
+                    float v[EPL];
+#pragma unroll
+                    for (int c = 0; c < EPL; ++c) v[c] = gsum[c] * m;
+                    atomic_add_row<XG, EPL>(p.grad_x, (int64_t)leaf[q * k2 + e] * p.D + d, v);
+                }
             }
         }
     }
@@ -258,10 +350,8 @@ static int env_int(const char* name, int fallback) {
     return v ? std::atoi(v) : fallback;
 }
 
-hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
-    BwdParams p;
-    p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
-    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
+template <typename GT, typename XG>
+static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hipStream_t stream) {
     if (!a.ids2) {
         // seeds per wave: more seeds per workgroup merge more hub traffic, but small batches
         // must still spread over the chip
@@ -276,15 +366,32 @@ hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
         if (no_hot) hot_rows = 0;
         const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
         const size_t lds = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave) + sizeof(float) * (size_t)hot_rows * a.D;
-        hipLaunchKernelGGL(bwd1_kernel, dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
+        hipLaunchKernelGGL((bwd1_kernel<GT, XG>), dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
     } else {
         static const int forced = env_int("FSA_BWD2_WAVES", 0);
         int nw = (forced >= 1 && forced <= 8) ? forced : (a.k1 < 8 ? a.k1 : 8);
         const int nq_max = (a.k1 + nw - 1) / nw;
         const size_t lds = sizeof(int) * ((size_t)nw * (2 * nq_max * a.k2 + 2 * nq_max) + nw);
-        hipLaunchKernelGGL(bwd2_kernel, dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
+        hipLaunchKernelGGL((bwd2_kernel<GT, XG>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
+    BwdParams p;
+    p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
+    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
+    // kinds: 0 fp32, 1 bfloat16, 2 fp16.  A 16-bit grad_x takes gradients of its own type or fp32.
+    switch (a.grad_kind * 3 + a.grad_x_kind) {
+        case 0 * 3 + 0: return launch_backward_typed<g_f32, g_f32>(a, p, stream);
+        case 1 * 3 + 0: return launch_backward_typed<g_bf16, g_f32>(a, p, stream);
+        case 2 * 3 + 0: return launch_backward_typed<g_f16, g_f32>(a, p, stream);
+        case 0 * 3 + 1: return launch_backward_typed<g_f32, g_bf16>(a, p, stream);
+        case 1 * 3 + 1: return launch_backward_typed<g_bf16, g_bf16>(a, p, stream);
+        case 0 * 3 + 2: return launch_backward_typed<g_f32, g_f16>(a, p, stream);
+        case 2 * 3 + 2: return launch_backward_typed<g_f16, g_f16>(a, p, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace fsa

@@ -115,6 +115,7 @@ __device__ __forceinline__ int64_t load_indptr(const void* indptr, int64_t i) {
 // ---------------------------------------------------------------------------------------
 struct f32_t { float v; };
 struct bf16_t { uint16_t v; };
+struct f16_t { uint16_t v; };
 
 template <int VB> struct RawOf;
 template <> struct RawOf<16> { using type = uint4; };
@@ -185,6 +186,63 @@ template <int VB> struct Chunk<bf16_t, VB> {
         const bf16x2 b = __builtin_convertvector(v, bf16x2);
         uint32_t u;
         __builtin_memcpy(&u, &b, sizeof u);
+        return u;
+    }
+    static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {
+        Raw r;
+        if constexpr (VB == 16) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); r.z = pack2(v[4], v[5]); r.w = pack2(v[6], v[7]); }
+        else if constexpr (VB == 8) { r.x = pack2(v[0], v[1]); r.y = pack2(v[2], v[3]); }
+        else if constexpr (VB == 4) { r = pack2(v[0], v[1]); }
+        else { r = (uint16_t)(pack2(v[0], 0.0f) & 0xffffu); }
+        return r;
+    }
+};
+
+// IEEE half: widened and narrowed a pair at a time by the hardware converts (narrowing is
+// round-to-nearest-even).
+template <int VB> struct Chunk<f16_t, VB> {
+    static constexpr int VE = VB / 2;
+    using Raw = typename RawOf<VB>::type;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ f32x2 widen(uint32_t w) {
+        f16x2 h;
+        __builtin_memcpy(&h, &w, sizeof h);
+        return __builtin_convertvector(h, f32x2);
+    }
+    static __device__ __forceinline__ float widen1(uint16_t w) {
+        _Float16 h;
+        __builtin_memcpy(&h, &w, sizeof h);
+        return (float)h;
+    }
+    static __device__ __forceinline__ void add2(float& lo, float& hi, uint32_t w) {
+        const f32x2 f = widen(w);
+        lo += f[0];
+        hi += f[1];
+    }
+    static __device__ __forceinline__ void add(float (&acc)[VE], const Raw& r) {
+        if constexpr (VB == 16) { add2(acc[0], acc[1], r.x); add2(acc[2], acc[3], r.y); add2(acc[4], acc[5], r.z); add2(acc[6], acc[7], r.w); }
+        else if constexpr (VB == 8) { add2(acc[0], acc[1], r.x); add2(acc[2], acc[3], r.y); }
+        else if constexpr (VB == 4) { add2(acc[0], acc[1], r); }
+        else { acc[0] += widen1(r); }
+    }
+    static __device__ __forceinline__ void fma2(float& lo, float& hi, uint32_t v, float w) {
+        const f32x2 f = widen(v);
+        lo = fmaf(w, f[0], lo);
+        hi = fmaf(w, f[1], hi);
+    }
+    // acc += w * row chunk (weighted mean)
+    static __device__ __forceinline__ void fma(float (&acc)[VE], const Raw& r, float w) {
+        if constexpr (VB == 16) { fma2(acc[0], acc[1], r.x, w); fma2(acc[2], acc[3], r.y, w); fma2(acc[4], acc[5], r.z, w); fma2(acc[6], acc[7], r.w, w); }
+        else if constexpr (VB == 8) { fma2(acc[0], acc[1], r.x, w); fma2(acc[2], acc[3], r.y, w); }
+        else if constexpr (VB == 4) { fma2(acc[0], acc[1], r, w); }
+        else { acc[0] = fmaf(w, widen1(r), acc[0]); }
+    }
+    static __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+        const f32x2 v = {lo, hi};
+        const f16x2 h = __builtin_convertvector(v, f16x2);
+        uint32_t u;
+        __builtin_memcpy(&u, &h, sizeof u);
         return u;
     }
     static __device__ __forceinline__ Raw pack(const float (&v)[VE]) {

@@ -457,19 +457,27 @@ hipError_t launch_forward(const FwdArgs& a, hipStream_t stream) {
     p.seeds = a.seeds; p.ids1 = a.ids1; p.ids2 = a.ids2;
     p.out = static_cast<char*>(a.out); p.out_h1 = static_cast<char*>(a.out_h1);
     p.out_ids1 = a.out_ids1; p.out_ids2 = a.out_ids2;
-    p.B = a.B; p.row_bytes = a.D * (a.x_is_bf16 ? 2 : 4); p.seed = a.seed;
+    p.B = a.B; p.row_bytes = a.D * (a.x_kind == 0 ? 4 : 2); p.seed = a.seed;
     p.k1 = a.k1; p.k2 = a.k2; p.chunks = a.geom.chunks; p.sub = a.geom.sub;
     p.sub_shift = __builtin_ctz((unsigned)a.geom.sub); p.indptr_is64 = a.indptr_is64;
 #ifdef FSA_TRACE
     { const char* t = std::getenv("FSA_TRACE_PTR"); p.trace = t ? reinterpret_cast<long long*>(std::strtoull(t, nullptr, 16)) : nullptr; }
 #endif
     const int vb = a.geom.vec_bytes;
-    if (a.x_is_bf16) {
+    if (a.x_kind == 1) {
         switch (vb) {
             case 16: return launch_typed<bf16_t, 16>(a, p, stream);
             case 8:  return launch_typed<bf16_t, 8>(a, p, stream);
             case 4:  return launch_typed<bf16_t, 4>(a, p, stream);
             default: return launch_typed<bf16_t, 2>(a, p, stream);
+        }
+    }
+    if (a.x_kind == 2) {
+        switch (vb) {
+            case 16: return launch_typed<f16_t, 16>(a, p, stream);
+            case 8:  return launch_typed<f16_t, 8>(a, p, stream);
+            case 4:  return launch_typed<f16_t, 4>(a, p, stream);
+            default: return launch_typed<f16_t, 2>(a, p, stream);
         }
     }
     switch (vb) {

@@ -16,7 +16,7 @@ struct RowGeom {
 
 struct FwdArgs {
     const void* indptr; int indptr_is64; const int32_t* indices;
-    const void* x; int x_is_bf16; int64_t D;
+    const void* x; int x_kind; int64_t D;      // x_kind: 0 fp32, 1 bfloat16, 2 fp16
     const int32_t* seeds; int64_t B; int k1; int k2; int hops; uint64_t seed;
     const int32_t* ids1; const int32_t* ids2;   // replay inputs (indptr == nullptr selects replay)
     void* out; void* out_h1; int32_t* out_ids1; int32_t* out_ids2;
@@ -24,8 +24,10 @@ struct FwdArgs {
 };
 
 struct BwdArgs {
-    const float* grad_out; const float* grad_h1; const int32_t* ids1; const int32_t* ids2;
-    int64_t B; int k1; int k2; int64_t D; float* grad_x;
+    const void* grad_out; const void* grad_h1; const int32_t* ids1; const int32_t* ids2;
+    int64_t B; int k1; int k2; int64_t D; void* grad_x;
+    int grad_kind = 0;      // element type of grad_out / grad_h1: 0 fp32, 1 bfloat16, 2 fp16
+    int grad_x_kind = 0;    // element type of grad_x
 };
 
 // Weighted mean: the same launches with per-edge weights (edge_w aligned with indices) and

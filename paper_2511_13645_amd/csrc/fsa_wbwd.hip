@@ -150,8 +150,10 @@ __global__ __launch_bounds__(512) void wbwd2_kernel(const WBwdParams p) {
 
 hipError_t launch_backward_weighted(const BwdArgs& a, const WeightArgs& w, hipStream_t stream) {
     WBwdParams p;
-    p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
-    p.w1 = w.w1; p.w2 = w.w2; p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
+    // the weighted backward is fp32 on both sides
+    p.grad_out = static_cast<const float*>(a.grad_out); p.grad_h1 = static_cast<const float*>(a.grad_h1);
+    p.ids1 = a.ids1; p.ids2 = a.ids2;
+    p.w1 = w.w1; p.w2 = w.w2; p.grad_x = static_cast<float*>(a.grad_x); p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
     if (!a.ids2) {
         const int wpb = 4;
         const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);

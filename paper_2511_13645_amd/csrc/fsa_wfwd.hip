@@ -415,16 +415,24 @@ hipError_t launch_forward_weighted(const FwdArgs& a, const WeightArgs& w, hipStr
     p.seeds = a.seeds; p.ids1 = a.ids1; p.ids2 = a.ids2; p.w1 = w.w1; p.w2 = w.w2;
     p.out = static_cast<char*>(a.out); p.out_h1 = static_cast<char*>(a.out_h1);
     p.out_ids1 = a.out_ids1; p.out_ids2 = a.out_ids2; p.out_w1 = w.out_w1; p.out_w2 = w.out_w2;
-    p.B = a.B; p.row_bytes = a.D * (a.x_is_bf16 ? 2 : 4); p.seed = a.seed;
+    p.B = a.B; p.row_bytes = a.D * (a.x_kind == 0 ? 4 : 2); p.seed = a.seed;
     p.k1 = a.k1; p.k2 = a.k2; p.chunks = a.geom.chunks; p.sub = a.geom.sub;
     p.sub_shift = __builtin_ctz((unsigned)a.geom.sub); p.indptr_is64 = a.indptr_is64;
     const int vb = a.geom.vec_bytes;
-    if (a.x_is_bf16) {
+    if (a.x_kind == 1) {
         switch (vb) {
             case 16: return launch_typed_w<bf16_t, 16>(a, p, stream);
             case 8:  return launch_typed_w<bf16_t, 8>(a, p, stream);
             case 4:  return launch_typed_w<bf16_t, 4>(a, p, stream);
             default: return launch_typed_w<bf16_t, 2>(a, p, stream);
+        }
+    }
+    if (a.x_kind == 2) {
+        switch (vb) {
+            case 16: return launch_typed_w<f16_t, 16>(a, p, stream);
+            case 8:  return launch_typed_w<f16_t, 8>(a, p, stream);
+            case 4:  return launch_typed_w<f16_t, 4>(a, p, stream);
+            default: return launch_typed_w<f16_t, 2>(a, p, stream);
         }
     }
     switch (vb) {

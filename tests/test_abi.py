@@ -64,9 +64,10 @@ def test_forward_rejects_bad_arguments(fsa):
     assert _fwd(fsa, fan=[0, 3]) == -2 and _fwd(fsa, fan=[65, 3]) == -2 and _fwd(fsa, fan=[5, 65]) == -2
     assert _fwd(fsa, fan=[5, -1]) == -2
     assert _fwd(fsa, D=0) == -2 and _fwd(fsa, B=-1) == -2 and _fwd(fsa, n=0) == -2
-    assert _fwd(fsa, xt=2) == -3 and _fwd(fsa, itype=5) == -3
+    assert _fwd(fsa, xt=3) == -3 and _fwd(fsa, itype=5) == -3
     assert _fwd(fsa, x=FAKE + 2) == -4               # fp32 table on a 2-byte boundary
     assert _fwd(fsa, x=FAKE + 1, xt=1) == -4         # bf16 table on an odd address
+    assert _fwd(fsa, x=FAKE + 1, xt=2) == -4         # fp16 likewise
     assert _fwd(fsa, indptr=FAKE + 4, itype=1) == -4
     assert _fwd(fsa, ids1=FAKE + 2) == -4
     # 1-hop takes no hop-2 outputs
@@ -94,6 +95,23 @@ def test_replay_and_backward_reject_bad_arguments(fsa):
     assert bw(ids2=None, gh=FAKE) == -2
     assert bw(gx=FAKE + 2) == -4
     assert bw(B=0) == 0
+
+
+def test_reduced_precision_backward_rejects_bad_arguments(fsa):
+    L = fsa.lib()
+
+    def bw(**k):
+        a = dict(go=FAKE, gh=FAKE, gt=1, ids1=FAKE, ids2=FAKE, B=4, k1=3, k2=2, D=8, gx=FAKE, xt=0, n=10, s=None)
+        a.update(k)
+        return L.fsa_mean_bwd_lp(*[a[n] for n in ("go", "gh", "gt", "ids1", "ids2", "B", "k1", "k2", "D", "gx", "xt", "n", "s")])
+    assert bw(go=None) == -1 and bw(ids1=None) == -1 and bw(gx=None) == -1
+    assert bw(gt=3) == -3 and bw(xt=5) == -3
+    assert bw(gt=1, xt=2) == -3 and bw(gt=2, xt=1) == -3      # a 16-bit grad_x takes its own type or fp32
+    assert bw(D=7) == -2 and bw(gt=0, xt=1, D=7) == -2        # element pairs need an even D
+    assert bw(k1=0) == -2 and bw(ids2=None, gh=FAKE) == -2
+    assert bw(gx=FAKE + 2, xt=1) == -4 and bw(go=FAKE + 2) == -4
+    for gt, xt in ((0, 0), (1, 0), (2, 0), (0, 1), (1, 1), (0, 2), (2, 2)):
+        assert bw(gt=gt, xt=xt, B=0) == 0
 
 
 def test_binding_fails_loudly_without_library(fsa, monkeypatch):
