@@ -128,7 +128,9 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
  *                         hardware atomics, each of which rounds the running sum again: with
  *                         n additions into an element the error is bounded by about
  *                         (n + 1) * 2^-8 (bf16) or (n + 1) * 2^-10 (fp16) times the sum of
- *                         the absolute contributions, whatever way the atomic unit rounds.
+ *                         the absolute contributions, whatever way the atomic unit rounds
+ *                         (plus (n + 1) subnormal spacings, 2^-24 for fp16, where values
+ *                         fall below the smallest normal number).
  *                         fp16 sums can overflow to infinity.
  * With any 16-bit operand D must be even (FSA_ERR_ARG otherwise) and the arrays 4-byte
  * aligned: lanes read and add element pairs.  grad_dtype == grad_x_dtype == FSA_F32 is

@@ -11,7 +11,10 @@ steps the HIP path is documented to take:
   backward, 16-bit grad_x  each contribution is rounded once and each of the n atomic adds
                          into an element rounds the running sum, at most one ulp each whatever
                          the rounding mode: |error| <= (n + 1) * ulp * sum|contribution|, with
-                         ulp = 2^-8 (bf16) or 2^-10 (fp16); n is counted from the IDs."""
+                         ulp = 2^-8 (bf16) or 2^-10 (fp16); n is counted from the IDs.  Below the
+                         smallest normal number a rounding is absolute, not relative: each of
+                         the n + 1 roundings may also cost one subnormal spacing (2^-24 for fp16,
+                         2^-133 for bf16)."""
 import numpy as np
 import pytest
 import torch
@@ -23,6 +26,7 @@ pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
 ULP = {torch.bfloat16: 2.0 ** -8, torch.float16: 2.0 ** -10}
+SUBNORMAL_STEP = {torch.bfloat16: 2.0 ** -133, torch.float16: 2.0 ** -24}
 
 
 @pytest.fixture(scope="module")
@@ -101,14 +105,14 @@ def lowprec_case(fsa, orc, indptr, indices, n, D, seeds, fan, g_dtype, x_dtype, 
         n_add = adds_per_row(h_ids1, h_ids2, n).astype(np.float64)[:, None]
         got = to_f64(gx)
         assert np.isfinite(got).all(), what
-        bound = (n_add + 1.0) * ULP[x_dtype] * mag
+        bound = (n_add + 1.0) * (ULP[x_dtype] * mag + SUBNORMAL_STEP[x_dtype])
         err = np.abs(got - ref)
         assert (err <= bound).all(), "%s: worst excess %g at %s" % (
             what, float((err - bound).max()), np.unravel_index(np.argmax(err - bound), err.shape))
         # the bound is not vacuous: rows that took a single addition are within one rounding
         once = n_add[:, 0] == 1
         if once.any():
-            assert (err[once] <= 2.0 * ULP[x_dtype] * mag[once]).all(), what + " single-add rows"
+            assert (err[once] <= 2.0 * (ULP[x_dtype] * mag[once] + SUBNORMAL_STEP[x_dtype])).all(), what + " single-add rows"
         # and rows that took none are untouched
         assert (got[n_add[:, 0] == 0] == 0).all(), what + " untouched rows"
 
