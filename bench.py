@@ -92,7 +92,7 @@ def main() -> int:
                     "absent, loaded if present (counter runs use it: rocprofv3 --pmc does not survive the "
                     "in-process generation of the full-size graph on this image)")
     ap.add_argument("--paths", action="store_true",
-                    help="also time the replay forward and (fp32 tables) the backward on the same batches")
+                    help="also time the replay forward and the backward variants on the same batches")
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes: time the forward at each, "
                     "with and without ID / per-slot emission, on the same graph")
     ap.add_argument("--feature-dtype", default="", choices=["", "f32", "bf16"],
@@ -250,17 +250,26 @@ def main() -> int:
         other_paths["replay_forward"] = {"launch_us": r_ms * 1e3, "rows_per_s": rows_p / (r_ms * 1e-3),
                                          "hbm_gbps": r_alg / (r_ms * 1e-3) / 1e9,
                                          "frac": r_alg / (r_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        # backward: fp32 throughout (fp32 tables), then 16-bit upstream gradients into an fp32
+        # master gradient, then a bf16 grad_x by packed atomics
+        combos = [("backward_bf16_grads_f32_master", torch.bfloat16, torch.float32),
+                  ("backward_bf16_packed_atomics", torch.bfloat16, torch.bfloat16)]
         if x.dtype == torch.float32:
-            g_out = synth.upstream_grad((B, D), seed=3, device=dev)
-            g_h1 = synth.upstream_grad((B, k1, D), seed=4, device=dev) if hops == 2 else None
-            grad_x = torch.zeros((N, D), dtype=torch.float32, device=dev)
-            bwd = L.fsa_mean_bwd
+            combos.insert(0, ("backward", torch.float32, torch.float32))
+        if D % 2:
+            combos = [c for c in combos if c[1] == torch.float32 and c[2] == torch.float32]
+        code = {torch.float32: binding.FSA_F32, torch.bfloat16: binding.FSA_BF16}
+        bwd_lp = L.fsa_mean_bwd_lp
+        for key, g_dt, gx_dt in combos:
+            g_out = synth.upstream_grad((B, D), seed=3, device=dev).to(g_dt)
+            g_h1 = synth.upstream_grad((B, k1, D), seed=4, device=dev).to(g_dt) if hops == 2 else None
+            grad_x = torch.zeros((N, D), dtype=gx_dt, device=dev)
 
             def run_bwd(i):
-                rc = bwd(g_out.data_ptr(), None if g_h1 is None else g_h1.data_ptr(), id1_ptrs[i], id2_ptrs[i],
-                         B, k1, k2, D, grad_x.data_ptr(), N, stream)
+                rc = bwd_lp(g_out.data_ptr(), None if g_h1 is None else g_h1.data_ptr(), code[g_dt],
+                            id1_ptrs[i], id2_ptrs[i], B, k1, k2, D, grad_x.data_ptr(), code[gx_dt], N, stream)
                 if rc != 0:
-                    raise RuntimeError("fsa_mean_bwd -> %d" % rc)
+                    raise RuntimeError("fsa_mean_bwd_lp -> %d" % rc)
             for i in range(warmup, warmup + 2):
                 run_bwd(i)
             torch.cuda.synchronize()
@@ -270,12 +279,13 @@ def main() -> int:
             e1.record()
             torch.cuda.synchronize()
             b_ms = e0.elapsed_time(e1) / n_p
-            payload = rows_p * D * 4                # bytes added into grad_x by atomics
-            b_alg = 2 * payload + 4 * rows_p + B * D * 4 + (B * k1 * D * 4 if hops == 2 else 0)
-            other_paths["backward"] = {"launch_us": b_ms * 1e3, "rows_per_s": rows_p / (b_ms * 1e-3),
-                                       "atomic_payload_gbps": payload / (b_ms * 1e-3) / 1e9,
-                                       "hbm_gbps": b_alg / (b_ms * 1e-3) / 1e9,
-                                       "frac": b_alg / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            ge, xe = g_out.element_size(), grad_x.element_size()
+            payload = rows_p * D * xe               # bytes added into grad_x by atomics
+            b_alg = 2 * payload + 4 * rows_p + B * D * ge + (B * k1 * D * ge if hops == 2 else 0)
+            other_paths[key] = {"launch_us": b_ms * 1e3, "rows_per_s": rows_p / (b_ms * 1e-3),
+                                "atomic_payload_gbps": payload / (b_ms * 1e-3) / 1e9,
+                                "hbm_gbps": b_alg / (b_ms * 1e-3) / 1e9,
+                                "frac": b_alg / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
             del g_out, g_h1, grad_x
         log("[bench] other paths: %s" % json.dumps(other_paths))
 

@@ -132,9 +132,9 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
  *                         (plus (n + 1) subnormal spacings, 2^-24 for fp16, where values
  *                         fall below the smallest normal number).
  *                         fp16 sums can overflow to infinity.
- * With any 16-bit operand D must be even (FSA_ERR_ARG otherwise) and the arrays 4-byte
- * aligned: lanes read and add element pairs.  grad_dtype == grad_x_dtype == FSA_F32 is
- * exactly fsa_mean_bwd.  grad_x is accumulated into; the order of additions varies.
+ * With a 16-bit grad_x D must be even (FSA_ERR_ARG otherwise) and every array 4-byte aligned:
+ * lanes read and add element pairs.  grad_dtype == grad_x_dtype == FSA_F32 is exactly
+ * fsa_mean_bwd.  grad_x is accumulated into; the order of additions varies.
  */
 int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
                     const int32_t* ids1, const int32_t* ids2,

@@ -131,10 +131,11 @@ int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
     if (grad_x_dtype != FSA_F32 && grad_dtype != FSA_F32 && grad_dtype != grad_x_dtype) return FSA_ERR_DTYPE;
     if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
     if (!ids2 && grad_h1) return FSA_ERR_ARG;
-    const bool pairs = grad_dtype != FSA_F32 || grad_x_dtype != FSA_F32;
-    if (pairs && (D & 1)) return FSA_ERR_ARG;                  // lanes own element pairs
-    // 16-bit arrays are accessed a pair (4 bytes) at a time
-    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4))
+    const bool pairs = grad_x_dtype != FSA_F32;                // lanes own element pairs
+    if (pairs && (D & 1)) return FSA_ERR_ARG;
+    const uintptr_t g_align = pairs ? 4 : (uintptr_t)elem_bytes(grad_dtype);
+    if (!aligned(grad_out, g_align) || !aligned(grad_h1, g_align) || !aligned(grad_x, 4) || !aligned(ids1, 4) ||
+        !aligned(ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
 

@@ -22,21 +22,22 @@ struct BwdParams {
 };
 
 // ---------------------------------------------------------------------------------------
-// Element types of the incoming gradients (GT) and of grad_x (XG).  With fp32 on both sides a
-// lane owns one element of the row (EPL = 1) and adds it with global_atomic_add_f32.  As soon
-// as one side is 16-bit a lane owns two consecutive elements (EPL = 2; D is even): 16-bit
-// gradients are read a pair per 4-byte load, and a 16-bit grad_x takes the pair in ONE packed
-// atomic (global_atomic_pk_add_bf16 / _f16), which halves the number of atomic operations per
-// row -- the L2 atomic unit, not bandwidth, bounds this kernel.  Products and sums before the
-// atomic are fp32; the value is rounded to the 16-bit type once (nearest-even) and every
-// packed atomic rounds the running sum again.
+// Element types of the incoming gradients (GT) and of grad_x (XG).  With an fp32 grad_x a
+// lane owns one element of the row (EPL = 1), whatever the type of the incoming gradients, so
+// that one wave instruction of global_atomic_add_f32 covers 256 contiguous bytes (pairs per
+// lane would leave every instruction striding over twice as many cache lines: measured 1.7x
+// slower).  With a 16-bit grad_x a lane owns two consecutive elements (EPL = 2; D is even)
+// and adds the pair in ONE packed atomic (global_atomic_pk_add_bf16 / _f16), which halves the
+// number of atomic operations per row -- the L2 atomic unit, not bandwidth, bounds this
+// kernel.  Products and sums before the atomic are fp32; the value is rounded to the 16-bit
+// type once (nearest-even) and every packed atomic rounds the running sum again.
 // ---------------------------------------------------------------------------------------
 struct g_f32 { using T = float; };
 struct g_bf16 { using T = uint16_t; };
 struct g_f16 { using T = uint16_t; };
 
 template <typename GT, typename XG> struct Epl { static constexpr int value = 2; };
-template <> struct Epl<g_f32, g_f32> { static constexpr int value = 1; };
+template <typename GT> struct Epl<GT, g_f32> { static constexpr int value = 1; };
 
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -49,8 +50,16 @@ __device__ __forceinline__ void load_grad(const void* base, int64_t idx, float (
         const float* p = static_cast<const float*>(base) + idx;
 #pragma unroll
         for (int e = 0; e < EPL; ++e) g[e] = p[e];
+    } else if constexpr (EPL == 1) {
+        const uint16_t w = static_cast<const uint16_t*>(base)[idx];
+        if constexpr (std::is_same<GT, g_bf16>::value) {
+            g[0] = __uint_as_float((uint32_t)w << 16);
+        } else {
+            _Float16 h;
+            __builtin_memcpy(&h, &w, sizeof h);
+            g[0] = (float)h;
+        }
     } else {
-        static_assert(EPL == 2, "16-bit gradients are read in pairs");
         const uint32_t w = *reinterpret_cast<const uint32_t*>(static_cast<const uint16_t*>(base) + idx);
         if constexpr (std::is_same<GT, g_bf16>::value) {
             g[0] = __uint_as_float(w << 16);

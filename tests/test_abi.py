@@ -107,9 +107,10 @@ def test_reduced_precision_backward_rejects_bad_arguments(fsa):
     assert bw(go=None) == -1 and bw(ids1=None) == -1 and bw(gx=None) == -1
     assert bw(gt=3) == -3 and bw(xt=5) == -3
     assert bw(gt=1, xt=2) == -3 and bw(gt=2, xt=1) == -3      # a 16-bit grad_x takes its own type or fp32
-    assert bw(D=7) == -2 and bw(gt=0, xt=1, D=7) == -2        # element pairs need an even D
+    assert bw(xt=1, D=7) == -2 and bw(gt=0, xt=2, D=7) == -2  # element pairs need an even D
+    assert bw(D=7, B=0) == 0                                  # an fp32 grad_x does not
     assert bw(k1=0) == -2 and bw(ids2=None, gh=FAKE) == -2
-    assert bw(gx=FAKE + 2, xt=1) == -4 and bw(go=FAKE + 2) == -4
+    assert bw(gx=FAKE + 2, xt=1) == -4 and bw(go=FAKE + 1) == -4 and bw(go=FAKE + 2, xt=1) == -4
     for gt, xt in ((0, 0), (1, 0), (2, 0), (0, 1), (1, 1), (0, 2), (2, 2)):
         assert bw(gt=gt, xt=xt, B=0) == 0
 

@@ -64,3 +64,41 @@ def test_no_ids_without_grad_and_training_step_touches_sampled_rows_only():
     sampled[ids2[ids2 >= 0].long()] = True
     assert not (moved & ~sampled).any()
     assert moved.sum() > 0.5 * sampled.sum()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("fan,D", [([10], 40), ([6, 5], 40), ([6, 5], 33)])
+def test_autograd_with_16bit_tables(orc, dtype, fan, D):
+    """A 16-bit table gets a gradient of its own type (packed atomics; an odd D goes through an
+    fp32 master and is rounded once), or the caller's fp32 master gradient is accumulated into."""
+    from paper_2511_13645_amd.autograd import fused_sample_mean
+    dev = "cuda:0"
+    n, B = 2000, 300
+    ulp = {torch.bfloat16: 2.0 ** -8, torch.float16: 2.0 ** -10}[dtype]
+    indptr, indices = _graph(n, 1)
+    d_indptr, d_indices = torch.from_numpy(indptr).to(dev), torch.from_numpy(indices).to(dev)
+    rng = np.random.default_rng(2)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32)).to(dev).to(dtype).requires_grad_(True)
+    seeds = torch.from_numpy(rng.integers(0, n, B).astype(np.int32)).to(dev)
+    w_out = torch.from_numpy(rng.standard_normal((B, D)).astype(np.float32)).to(dev).to(dtype)
+
+    out, _, ids1, ids2 = fused_sample_mean(x, d_indptr, d_indices, seeds, fan, 11)
+    (out * w_out).sum().backward()
+    torch.cuda.synchronize()
+    assert x.grad.dtype == dtype
+    h1 = ids1.cpu().numpy()
+    h2 = None if ids2 is None else ids2.cpu().numpy()
+    ref = orc.mean_bwd(to_f64(w_out), h1, h2, None, num_nodes=n)
+    mag = orc.mean_bwd(np.abs(to_f64(w_out)), h1, h2, None, num_nodes=n)
+    leaves = h1 if h2 is None else h2
+    n_add = np.bincount(leaves[leaves >= 0], minlength=n).astype(np.float64)[:, None]
+    err = np.abs(to_f64(x.grad) - ref)
+    assert (err <= (n_add + 1) * (ulp * mag + 2.0 ** -24)).all()
+
+    master = torch.zeros((n, D), dtype=torch.float32, device=dev)
+    x2 = x.detach().clone().requires_grad_(True)
+    out2, _, _, _ = fused_sample_mean(x2, d_indptr, d_indices, seeds, fan, 11, master_grad=master)
+    (out2 * w_out).sum().backward()
+    torch.cuda.synchronize()
+    assert x2.grad is None
+    assert_close(to_f64(master), ref, mag, 1e-5, "master gradient %s fan=%s" % (dtype, fan))
