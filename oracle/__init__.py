@@ -70,6 +70,14 @@ def lib() -> ctypes.CDLL:
         L.orc_wmean_replay_fwd.restype = ctypes.c_int
         L.orc_wmean_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, vp, i64]
         L.orc_wmean_bwd.restype = ctypes.c_int
+        L.orc_sample_mean3_fwd.argtypes = [vp, ctypes.c_int, vp, i64, vp, ctypes.c_int, i64, vp, i64, vp, u64,
+                                           vp, vp, vp, vp, vp, vp, vp, vp]
+        L.orc_sample_mean3_fwd.restype = ctypes.c_int
+        L.orc_mean3_replay_fwd.argtypes = [vp, ctypes.c_int, i64, i64, vp, vp, vp, i64, i32, i32, i32,
+                                           vp, vp, vp, vp, vp]
+        L.orc_mean3_replay_fwd.restype = ctypes.c_int
+        L.orc_mean3_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, vp, i64]
+        L.orc_mean3_bwd.restype = ctypes.c_int
         L.orc_round_to_bf16.argtypes = [vp, i64, vp]
         L.orc_round_to_bf16.restype = None
         L.orc_round_to_f32.argtypes = [vp, i64, vp]
@@ -199,6 +207,59 @@ def mean_bwd(grad_out, ids1, ids2=None, grad_h1=None, *, num_nodes: int, grad_x=
                             _vp(grad_x), num_nodes)
     if rc != 0:
         raise ValueError("orc_mean_bwd failed with %d" % rc)
+    return grad_x
+
+
+def sample_mean3_fwd(indptr, indices, x, seeds, fanouts, seed, *, bf16=False, want_h2=True):
+    """Three hops.  Returns a dict: out, out_h1, out_h2 | None, out_m1 (float64), ids1, ids2, ids3, cnt2."""
+    indptr = _c(indptr)
+    indices = _c(indices, np.int32)
+    x = _c(x)
+    seeds = _c(seeds, np.int32)
+    fan = np.asarray(list(fanouts), dtype=np.int32)
+    if fan.size != 3:
+        raise ValueError("three fanouts expected")
+    k1, k2, k3 = (int(v) for v in fan)
+    N, D, B = indptr.shape[0] - 1, x.shape[1], seeds.shape[0]
+    r = {"out": np.zeros((B, D)), "out_h1": np.zeros((B, k1, D)),
+         "out_h2": np.zeros((B, k1, k2, D)) if want_h2 else None, "out_m1": np.zeros((B, D)),
+         "ids1": np.full((B, k1), -7, dtype=np.int32), "ids2": np.full((B, k1, k2), -7, dtype=np.int32),
+         "ids3": np.full((B, k1, k2, k3), -7, dtype=np.int32), "cnt2": np.full((B, k1), -7, dtype=np.int32)}
+    rc = lib().orc_sample_mean3_fwd(_vp(indptr), _indptr_type(indptr), _vp(indices), N, _vp(x), _x_type(x, bf16), D,
+                                    _vp(seeds), B, _vp(fan), seed, _vp(r["out"]), _vp(r["out_h1"]), _vp(r["out_h2"]),
+                                    _vp(r["out_m1"]), _vp(r["ids1"]), _vp(r["ids2"]), _vp(r["ids3"]), _vp(r["cnt2"]))
+    if rc != 0:
+        raise ValueError("orc_sample_mean3_fwd failed with %d" % rc)
+    return r
+
+
+def mean3_replay_fwd(x, ids1, ids2, ids3, *, bf16=False, want_h2=True):
+    x = _c(x)
+    ids1, ids2, ids3 = _c(ids1, np.int32), _c(ids2, np.int32), _c(ids3, np.int32)
+    B, k1, k2, k3 = ids3.shape
+    D = x.shape[1]
+    r = {"out": np.zeros((B, D)), "out_h1": np.zeros((B, k1, D)),
+         "out_h2": np.zeros((B, k1, k2, D)) if want_h2 else None, "out_m1": np.zeros((B, D)),
+         "cnt2": np.full((B, k1), -7, dtype=np.int32)}
+    rc = lib().orc_mean3_replay_fwd(_vp(x), _x_type(x, bf16), D, x.shape[0], _vp(ids1), _vp(ids2), _vp(ids3),
+                                    B, k1, k2, k3, _vp(r["out"]), _vp(r["out_h1"]), _vp(r["out_h2"]),
+                                    _vp(r["out_m1"]), _vp(r["cnt2"]))
+    if rc != 0:
+        raise ValueError("orc_mean3_replay_fwd failed with %d" % rc)
+    return r
+
+
+def mean3_bwd(grad_out, ids1, ids2, ids3, *, grad_h1=None, grad_h2=None, grad_m1=None, num_nodes: int):
+    grad_out = _c(grad_out, np.float64)
+    ids1, ids2, ids3 = _c(ids1, np.int32), _c(ids2, np.int32), _c(ids3, np.int32)
+    B, k1, k2, k3 = ids3.shape
+    D = grad_out.shape[1]
+    opt = [None if g is None else _c(g, np.float64) for g in (grad_h1, grad_h2, grad_m1)]
+    grad_x = np.zeros((num_nodes, D), dtype=np.float64)
+    rc = lib().orc_mean3_bwd(_vp(grad_out), _vp(opt[0]), _vp(opt[1]), _vp(opt[2]), _vp(ids1), _vp(ids2), _vp(ids3),
+                             B, k1, k2, k3, D, _vp(grad_x), num_nodes)
+    if rc != 0:
+        raise ValueError("orc_mean3_bwd failed with %d" % rc)
     return grad_x
 
 

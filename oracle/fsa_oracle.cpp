@@ -423,6 +423,139 @@ int orc_wmean_bwd(const double* grad_out, const double* grad_h1,
 }
 
 // Round-to-nearest-even from double straight to the 8-bit significand of bfloat16.
+// ---- three hops (the nested mean of Sec. 3.2 taken one level deeper) -------------------
+
+// Prop. 1 for three levels of saved IDs: every mean is the plain mean of the named rows, and
+// an empty neighborhood leaves both the sum and the divisor of the level above.
+int orc_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                         int64_t B, int32_t k1, int32_t k2, int32_t k3,
+                         double* out, double* out_h1, double* out_h2, double* out_m1,
+                         int32_t* cnt2) {
+    if (!x || !ids1 || !ids2 || !ids3 || !out) return -1;
+    if (B < 0 || D <= 0 || k1 <= 0 || k2 <= 0 || k3 <= 0 || num_nodes <= 0) return -2;
+    std::vector<double> leaf_mean(static_cast<size_t>(D)), mid(static_cast<size_t>(D));
+    for (int64_t b = 0; b < B; ++b) {
+        double* out_b = out + b * D;
+        for (int64_t d = 0; d < D; ++d) out_b[d] = 0.0;
+        if (out_m1) mean_of_rows(x, x_dtype, D, ids1 + b * k1, k1, out_m1 + b * D);
+        int32_t live_j = 0;
+        for (int32_t j = 0; j < k1; ++j) {
+            const int64_t bj = b * k1 + j;
+            for (int64_t d = 0; d < D; ++d) mid[d] = 0.0;
+            int32_t live_i = 0;
+            for (int32_t i = 0; i < k2; ++i) {
+                const int64_t bji = bj * k2 + i;
+                int32_t c3 = 0;
+                if (ids1[bj] >= 0 && ids2[bji] >= 0)
+                    c3 = mean_of_rows(x, x_dtype, D, ids3 + bji * k3, k3, leaf_mean.data());
+                else
+                    for (int64_t d = 0; d < D; ++d) leaf_mean[d] = 0.0;
+                if (out_h2) std::memcpy(out_h2 + bji * D, leaf_mean.data(), sizeof(double) * D);
+                if (c3 > 0) {
+                    ++live_i;
+                    for (int64_t d = 0; d < D; ++d) mid[d] += leaf_mean[d];
+                }
+            }
+            if (live_i > 0)
+                for (int64_t d = 0; d < D; ++d) mid[d] /= static_cast<double>(live_i);
+            if (cnt2) cnt2[bj] = live_i;
+            if (out_h1) std::memcpy(out_h1 + bj * D, mid.data(), sizeof(double) * D);
+            if (live_i > 0) {
+                ++live_j;
+                for (int64_t d = 0; d < D; ++d) out_b[d] += mid[d];
+            }
+        }
+        if (live_j > 0)
+            for (int64_t d = 0; d < D; ++d) out_b[d] /= static_cast<double>(live_j);
+    }
+    return 0;
+}
+
+// Sampling for three hops: the seed's row with hop counter 0, the rows of its sampled
+// neighbors with counter 1, the rows of theirs with counter 2; then the means of the IDs.
+int orc_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, uint64_t seed,
+                         double* out, double* out_h1, double* out_h2, double* out_m1,
+                         int32_t* ids1, int32_t* ids2, int32_t* ids3, int32_t* cnt2) {
+    if (!indptr || !indices || !x || !seeds || !fanouts || !out || !ids1 || !ids2 || !ids3) return -1;
+    const int32_t k1 = fanouts[0], k2 = fanouts[1], k3 = fanouts[2];
+    if (B < 0 || D <= 0 || k1 <= 0 || k2 <= 0 || k3 <= 0 || num_nodes <= 0) return -2;
+    for (int64_t b = 0; b < B; ++b) {
+        const int64_t r = seeds[b];
+        if (r < 0 || r >= num_nodes) return -2;
+        int32_t* U = ids1 + b * k1;
+        orc_sample_row(indptr, indptr_type, indices, r, 0u, k1, seed, nullptr, U);
+        for (int32_t j = 0; j < k1; ++j) {
+            int32_t* V = ids2 + (b * k1 + j) * k2;
+            if (U[j] >= 0) orc_sample_row(indptr, indptr_type, indices, U[j], 1u, k2, seed, nullptr, V);
+            else for (int32_t i = 0; i < k2; ++i) V[i] = -1;
+            for (int32_t i = 0; i < k2; ++i) {
+                int32_t* W = ids3 + ((b * k1 + j) * k2 + i) * k3;
+                if (V[i] >= 0) orc_sample_row(indptr, indptr_type, indices, V[i], 2u, k3, seed, nullptr, W);
+                else for (int32_t l = 0; l < k3; ++l) W[l] = -1;
+            }
+        }
+    }
+    return orc_mean3_replay_fwd(x, x_dtype, D, num_nodes, ids1, ids2, ids3, B, k1, k2, k3,
+                                out, out_h1, out_h2, out_m1, cnt2);
+}
+
+// Adjoint of orc_mean3_replay_fwd with respect to X for upstream gradients on out, out_h1,
+// out_h2 and out_m1 (each nullable except grad_out), accumulated into grad_x.
+int orc_mean3_bwd(const double* grad_out, const double* grad_h1, const double* grad_h2,
+                  const double* grad_m1,
+                  const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                  int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                  double* grad_x, int64_t num_nodes) {
+    if (!grad_out || !ids1 || !ids2 || !ids3 || !grad_x) return -1;
+    if (B < 0 || D <= 0 || k1 <= 0 || k2 <= 0 || k3 <= 0 || num_nodes <= 0) return -2;
+    std::vector<int32_t> c3(static_cast<size_t>(k1) * k2), live_i(static_cast<size_t>(k1));
+    for (int64_t b = 0; b < B; ++b) {
+        int32_t live_j = 0;
+        for (int32_t j = 0; j < k1; ++j) {
+            live_i[j] = 0;
+            for (int32_t i = 0; i < k2; ++i) {
+                const int64_t bji = (b * k1 + j) * k2 + i;
+                int32_t c = 0;
+                if (ids1[b * k1 + j] >= 0 && ids2[bji] >= 0) c = count_valid(ids3 + bji * k3, k3);
+                c3[j * k2 + i] = c;
+                if (c > 0) ++live_i[j];
+            }
+            if (live_i[j] > 0) ++live_j;
+        }
+        for (int32_t j = 0; j < k1; ++j) {
+            if (live_i[j] == 0) continue;
+            for (int32_t i = 0; i < k2; ++i) {
+                const int32_t c = c3[j * k2 + i];
+                if (c == 0) continue;
+                const int64_t bji = (b * k1 + j) * k2 + i;
+                for (int32_t l = 0; l < k3; ++l) {
+                    const int32_t w = ids3[bji * k3 + l];
+                    if (w < 0) continue;
+                    for (int64_t d = 0; d < D; ++d) {
+                        double g = grad_out[b * D + d] / live_j;
+                        if (grad_h1) g += grad_h1[(b * k1 + j) * D + d];
+                        g /= live_i[j];
+                        if (grad_h2) g += grad_h2[bji * D + d];
+                        grad_x[static_cast<int64_t>(w) * D + d] += g / c;
+                    }
+                }
+            }
+        }
+        if (grad_m1) {
+            const int32_t c1 = count_valid(ids1 + b * k1, k1);
+            for (int32_t j = 0; j < k1; ++j) {
+                const int32_t u = ids1[b * k1 + j];
+                if (u < 0) continue;
+                for (int64_t d = 0; d < D; ++d) grad_x[static_cast<int64_t>(u) * D + d] += grad_m1[b * D + d] / c1;
+            }
+        }
+    }
+    return 0;
+}
+
 void orc_round_to_bf16(const double* src, int64_t n, uint16_t* dst) {
     for (int64_t i = 0; i < n; ++i) {
         const double v = src[i];

@@ -111,6 +111,35 @@ int orc_wmean_bwd(const double* grad_out, const double* grad_h1,
                   const int32_t* ids1, const int32_t* ids2, const float* w1, const float* w2,
                   int64_t B, int32_t k1, int32_t k2, int64_t D, double* grad_x, int64_t num_nodes);
 
+/* ---- three hops: the nested mean of Sec. 3.2 taken one level deeper (the paper discusses
+ * deeper hops under "Extension Feasibility" and "Limitations" without a formula; this is the
+ * same construction applied once more) ------------------------------------------------------
+ *   U = sample(seed, hop 0, k1);  V_j = sample(U[j], hop 1, k2);  W_ji = sample(V_j[i], hop 2, k3)
+ *   out_h2[b,j,i] = mean of X over W_ji                                  (zero row if empty)
+ *   out_h1[b,j]   = mean over the i with a non-empty W_ji of out_h2[b,j,i];  cnt2[b,j] = their number
+ *   out[b]        = mean over the j with cnt2[b,j] > 0 of out_h1[b,j]
+ *   out_m1[b]     = mean of X over U                    (the plain hop-1 mean, layer-wise SAGE)
+ * ids1 [B,k1], ids2 [B,k1,k2], ids3 [B,k1,k2,k3] are required (-1 padded, all -1 under an
+ * unused slot); out_h1, out_h2, out_m1, cnt2 may be NULL.  Parity pins: a fanout >= every
+ * degree reduces to products with the adjacency matrix computed by scipy (empty rows skipped
+ * level by level); every ids3 row equals orc_sample_row at hop 2; the adjoint identity and
+ * finite differences for the backward. */
+int orc_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, uint64_t seed,
+                         double* out, double* out_h1, double* out_h2, double* out_m1,
+                         int32_t* ids1, int32_t* ids2, int32_t* ids3, int32_t* cnt2);
+int orc_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                         int64_t B, int32_t k1, int32_t k2, int32_t k3,
+                         double* out, double* out_h1, double* out_h2, double* out_m1,
+                         int32_t* cnt2);
+int orc_mean3_bwd(const double* grad_out, const double* grad_h1, const double* grad_h2,
+                  const double* grad_m1,
+                  const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                  int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                  double* grad_x, int64_t num_nodes);
+
 /* Round fp64 values to bfloat16 bit patterns / fp32, round-to-nearest-even, directly from
  * the double (no intermediate float rounding). */
 void orc_round_to_bf16(const double* src, int64_t n, uint16_t* dst);
