@@ -142,6 +142,73 @@ int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
                     void* grad_x, int grad_x_dtype, int64_t num_nodes, void* stream);
 
 /*
+ * Layer-wise two-hop forward: fsa_sample_mean_fwd for fanouts (k1,k2) that ALSO emits the plain
+ * hop-1 mean  out_m1[b] = mean of X over the sampled hop-1 nodes U1(seed)  -- what a layer-wise
+ * GraphSAGE needs next to the nested mean, and the other way to read "the seed's mean" in a
+ * two-hop call (Sec. 3.2 defines the nested mean only).  out_m1 [B,D] x_dtype, required; the
+ * other arguments as in fsa_sample_mean_fwd with num_hops = 2.  Two launches on `stream`: the
+ * fused two-hop kernel and the one-hop kernel, which draws the same U1 because hop-0 draws
+ * depend only on (seed, node).  Replay: fsa_mean_replay_fwd(x, ids1) gives out_m1; backward:
+ * fsa_mean_bwd with (grad_m1, ids1) next to the two-hop call.
+ */
+int fsa_sample_mean_layerwise_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                                  int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                                  const int32_t* seeds, int64_t B, const int32_t* fanouts,
+                                  uint64_t seed, void* out, void* out_h1, void* out_m1,
+                                  int32_t* out_ids1, int32_t* out_ids2, void* stream);
+
+/*
+ * Three hops: the nested mean of Sec. 3.2 taken one level deeper (the paper names deeper hops
+ * as an extension with more traffic and synchronisation, Sec. 3.2 "Extension Feasibility" and
+ * Sec. 5; it gives no formula, so the same construction is applied once more):
+ *   U = sample(seed, hop 0, k1);  V_j = sample(U[j], hop 1, k2);  W_ji = sample(V_j[i], hop 2, k3)
+ *   out_h2[b,j,i] = mean of X over W_ji                                    (zero row if empty)
+ *   out_h1[b,j]   = mean over the i with non-empty W_ji of out_h2[b,j,i];  out_cnt2[b,j] = their number
+ *   out[b]        = mean over the j with out_cnt2[b,j] > 0 of out_h1[b,j]  (zero row if none)
+ *   out_m1[b]     = mean of X over U
+ * fanouts: HOST array of 3.  Required outputs: out [B,D], out_h1 [B,k1,D], out_m1 [B,D] (x_dtype),
+ * out_ids1 [B,k1], out_cnt2 [B,k1] (int32).  Optional: out_h2 [B,k1,k2,D], out_ids2 [B,k1,k2],
+ * out_ids3 [B,k1,k2,k3].  B*k1 must not exceed 2^31-1.
+ * Built layer-wise from the kernels above, three launches on `stream`: the one-hop kernel on
+ * the seeds; the fused two-hop kernel with the B*k1 hop-1 slots as roots and hop counters 1
+ * and 2 (so no gathered leaf tensor exists: the only intermediate is out_h1 itself); a mean
+ * over the slots of out_h1.  For 16-bit tables out is therefore formed from the ROUNDED out_h1
+ * rows (two roundings instead of one).
+ */
+int fsa_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, uint64_t seed,
+                         void* out, void* out_h1, void* out_h2, void* out_m1,
+                         int32_t* out_ids1, int32_t* out_ids2, int32_t* out_ids3, int32_t* out_cnt2,
+                         void* stream);
+
+/*
+ * Replay of the three-hop forward from saved IDs: the same three launches with the sampler
+ * replaced by loads, bitwise equal to fsa_sample_mean3_fwd on the IDs it emitted.  Holes (-1)
+ * may appear anywhere: (j,i) takes part iff ids1[b,j] >= 0, ids2[b,j,i] >= 0 and ids3[b,j,i,:]
+ * has a non-negative entry.  out_m1 and out_h2 may be NULL.
+ */
+int fsa_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                         int64_t B, int32_t k1, int32_t k2, int32_t k3,
+                         void* out, void* out_h1, void* out_h2, void* out_m1, int32_t* out_cnt2,
+                         void* stream);
+
+/*
+ * Backward of the three-hop forward with respect to the feature table (fp32 throughout):
+ *   grad_x[w,:] += ((grad_out[b,:]/c1_b + grad_h1[b,j,:]) / cnt2_bj + grad_h2[b,j,i,:]) / c3_bji
+ *   for every valid leaf w of a (j,i) that took part, and
+ *   grad_x[u,:] += grad_m1[b,:] / |U|  for every valid hop-1 node u.
+ * grad_h1 [B,k1,D], grad_h2 [B,k1,k2,D], grad_m1 [B,D] may be NULL.  `work` is a caller-owned
+ * scratch array of B*k1*D floats, overwritten (it carries the gradient of each hop-1 slot
+ * between the two kernels).  grad_x is accumulated into with fp32 atomics.
+ */
+int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                  const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                  int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                  float* grad_x, int64_t num_nodes, float* work, void* stream);
+
+/*
  * Weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted numerators
  * and denominators streamed per sampled neighborhood).  edge_weight [E] fp32 is aligned with
  * `indices`; weights must be finite and non-negative.  Sampling is unchanged -- the same

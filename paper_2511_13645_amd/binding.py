@@ -22,6 +22,7 @@ FSA_OK = 0
 FSA_KMAX = 64
 
 EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_mean_bwd_lp", "fsa_status_string",
+           "fsa_sample_mean_layerwise_fwd", "fsa_sample_mean3_fwd", "fsa_mean3_replay_fwd", "fsa_mean3_bwd",
            "fsa_sample_wmean_fwd", "fsa_wmean_replay_fwd", "fsa_wmean_bwd")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -57,6 +58,16 @@ def lib() -> ctypes.CDLL:
         L.fsa_wmean_replay_fwd.restype = ci
         L.fsa_wmean_bwd.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
         L.fsa_wmean_bwd.restype = ci
+        L.fsa_sample_mean_layerwise_fwd.argtypes = [vp, ci, vp, i64, vp, ci, i64, vp, i64, vp, u64,
+                                                    vp, vp, vp, vp, vp, vp]
+        L.fsa_sample_mean_layerwise_fwd.restype = ci
+        L.fsa_sample_mean3_fwd.argtypes = [vp, ci, vp, i64, vp, ci, i64, vp, i64, vp, u64,
+                                           vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.fsa_sample_mean3_fwd.restype = ci
+        L.fsa_mean3_replay_fwd.argtypes = [vp, ci, i64, i64, vp, vp, vp, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.fsa_mean3_replay_fwd.restype = ci
+        L.fsa_mean3_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, vp, i64, vp, vp]
+        L.fsa_mean3_bwd.restype = ci
         L.fsa_status_string.argtypes = [ci]
         L.fsa_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -217,6 +228,105 @@ def fsa_mean_bwd_lp(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[t
                                B, k1, k2, D, _ptr(grad_x), _x_dtype(grad_x), N, _stream(stream))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd_lp")
+    return grad_x
+
+
+def fsa_sample_mean_layerwise_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.Tensor, seeds: torch.Tensor,
+                                  fanouts: Sequence[int], seed: int, *, emit_h1: bool = True, emit_ids: bool = True,
+                                  stream: Optional[torch.cuda.Stream] = None):
+    """Two-hop forward that also returns the plain hop-1 mean: (out, out_h1 | None, out_m1, ids1 | None, ids2 | None)."""
+    _need(indptr, "indptr"); _need(indices, "indices", torch.int32); _need(x, "x"); _need(seeds, "seeds", torch.int32)
+    fan = [int(k) for k in fanouts]
+    if len(fan) != 2:
+        raise ValueError("two fanouts expected")
+    k1, k2 = fan
+    B, (N, D), dev = seeds.shape[0], x.shape, x.device
+    out = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_m1 = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev) if emit_h1 else None
+    ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev) if emit_ids else None
+    ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev) if emit_ids else None
+    fan_host = (ctypes.c_int32 * 2)(*fan)
+    rc = lib().fsa_sample_mean_layerwise_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N, _ptr(x), _x_dtype(x), D,
+                                             _ptr(seeds), B, ctypes.cast(fan_host, ctypes.c_void_p), int(seed) & (2**64 - 1),
+                                             _ptr(out), _ptr(out_h1), _ptr(out_m1), _ptr(ids1), _ptr(ids2), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_sample_mean_layerwise_fwd")
+    return out, out_h1, out_m1, ids1, ids2
+
+
+def fsa_sample_mean3_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.Tensor, seeds: torch.Tensor,
+                         fanouts: Sequence[int], seed: int, *, emit_h2: bool = False, emit_ids: bool = True,
+                         stream: Optional[torch.cuda.Stream] = None) -> dict:
+    """Three-hop forward.  Returns a dict: out, out_h1, out_h2 | None, out_m1, ids1, ids2 | None, ids3 | None, cnt2."""
+    _need(indptr, "indptr"); _need(indices, "indices", torch.int32); _need(x, "x"); _need(seeds, "seeds", torch.int32)
+    fan = [int(k) for k in fanouts]
+    if len(fan) != 3:
+        raise ValueError("three fanouts expected")
+    k1, k2, k3 = fan
+    B, (N, D), dev = seeds.shape[0], x.shape, x.device
+    r = {"out": torch.empty((B, D), dtype=x.dtype, device=dev),
+         "out_h1": torch.empty((B, k1, D), dtype=x.dtype, device=dev),
+         "out_h2": torch.empty((B, k1, k2, D), dtype=x.dtype, device=dev) if emit_h2 else None,
+         "out_m1": torch.empty((B, D), dtype=x.dtype, device=dev),
+         "ids1": torch.empty((B, k1), dtype=torch.int32, device=dev),
+         "ids2": torch.empty((B, k1, k2), dtype=torch.int32, device=dev) if emit_ids else None,
+         "ids3": torch.empty((B, k1, k2, k3), dtype=torch.int32, device=dev) if emit_ids else None,
+         "cnt2": torch.empty((B, k1), dtype=torch.int32, device=dev)}
+    fan_host = (ctypes.c_int32 * 3)(*fan)
+    rc = lib().fsa_sample_mean3_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N, _ptr(x), _x_dtype(x), D,
+                                    _ptr(seeds), B, ctypes.cast(fan_host, ctypes.c_void_p), int(seed) & (2**64 - 1),
+                                    _ptr(r["out"]), _ptr(r["out_h1"]), _ptr(r["out_h2"]), _ptr(r["out_m1"]),
+                                    _ptr(r["ids1"]), _ptr(r["ids2"]), _ptr(r["ids3"]), _ptr(r["cnt2"]), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_sample_mean3_fwd")
+    return r
+
+
+def fsa_mean3_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor, ids3: torch.Tensor, *,
+                         emit_h2: bool = False, emit_m1: bool = True,
+                         stream: Optional[torch.cuda.Stream] = None) -> dict:
+    _need(x, "x"); _need(ids1, "ids1", torch.int32); _need(ids2, "ids2", torch.int32); _need(ids3, "ids3", torch.int32)
+    B, k1, k2, k3 = ids3.shape
+    if tuple(ids1.shape) != (B, k1) or tuple(ids2.shape) != (B, k1, k2):
+        raise ValueError("ids1 / ids2 / ids3 shapes do not nest")
+    N, D = x.shape
+    dev = x.device
+    r = {"out": torch.empty((B, D), dtype=x.dtype, device=dev),
+         "out_h1": torch.empty((B, k1, D), dtype=x.dtype, device=dev),
+         "out_h2": torch.empty((B, k1, k2, D), dtype=x.dtype, device=dev) if emit_h2 else None,
+         "out_m1": torch.empty((B, D), dtype=x.dtype, device=dev) if emit_m1 else None,
+         "cnt2": torch.empty((B, k1), dtype=torch.int32, device=dev)}
+    rc = lib().fsa_mean3_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), _ptr(ids3), B, k1, k2, k3,
+                                    _ptr(r["out"]), _ptr(r["out_h1"]), _ptr(r["out_h2"]), _ptr(r["out_m1"]),
+                                    _ptr(r["cnt2"]), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean3_replay_fwd")
+    return r
+
+
+def fsa_mean3_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor, ids3: torch.Tensor, *,
+                  grad_h1: Optional[torch.Tensor] = None, grad_h2: Optional[torch.Tensor] = None,
+                  grad_m1: Optional[torch.Tensor] = None, grad_x: torch.Tensor,
+                  work: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Scatter-add the three-hop mean's gradient into grad_x [N,D] fp32 (accumulated, not zeroed)."""
+    _need(grad_out, "grad_out", torch.float32); _need(grad_x, "grad_x", torch.float32)
+    _need(ids1, "ids1", torch.int32); _need(ids2, "ids2", torch.int32); _need(ids3, "ids3", torch.int32)
+    B, k1, k2, k3 = ids3.shape
+    D = grad_out.shape[1]
+    for g, name, shape in ((grad_h1, "grad_h1", (B, k1, D)), (grad_h2, "grad_h2", (B, k1, k2, D)), (grad_m1, "grad_m1", (B, D))):
+        if g is not None:
+            _need(g, name, torch.float32)
+            if tuple(g.shape) != shape:
+                raise ValueError("%s must be %s" % (name, shape))
+    if work is None:
+        work = torch.empty((B, k1, D), dtype=torch.float32, device=grad_x.device)
+    elif work.numel() < B * k1 * D or work.dtype != torch.float32:
+        raise ValueError("work must hold B*k1*D floats")
+    rc = lib().fsa_mean3_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(grad_h2), _ptr(grad_m1), _ptr(ids1), _ptr(ids2), _ptr(ids3),
+                             B, k1, k2, k3, D, _ptr(grad_x), grad_x.shape[0], _ptr(work), _stream(stream))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean3_bwd")
     return grad_x
 
 

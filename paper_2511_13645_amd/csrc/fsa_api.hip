@@ -231,6 +231,151 @@ int fsa_wmean_bwd(const float* grad_out, const float* grad_h1,
     return fsa::launch_backward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
 }
 
+// ---- layer-wise and three-hop variants: chains of the kernels above on one stream ----------
+
+int fsa_sample_mean_layerwise_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                                  int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                                  const int32_t* seeds, int64_t B, const int32_t* fanouts,
+                                  uint64_t seed, void* out, void* out_h1, void* out_m1,
+                                  int32_t* out_ids1, int32_t* out_ids2, void* stream) {
+    if (B != 0 && !out_m1) return FSA_ERR_NULL;
+    if (x_dtype != FSA_F32 && x_dtype != FSA_BF16 && x_dtype != FSA_F16) return FSA_ERR_DTYPE;
+    if (!aligned(out_m1, (uintptr_t)elem_bytes(x_dtype))) return FSA_ERR_ALIGN;
+    // the two-hop call validates everything else before it launches; the one-hop call takes a
+    // subset of the same arguments and draws the same hop-1 IDs (same seed, hop counter 0)
+    if (int rc = fsa_sample_mean_fwd(indptr, indptr_type, indices, num_nodes, x, x_dtype, D, seeds, B, fanouts, 2,
+                                     seed, out, out_h1, out_ids1, out_ids2, stream))
+        return rc;
+    return fsa_sample_mean_fwd(indptr, indptr_type, indices, num_nodes, x, x_dtype, D, seeds, B, fanouts, 1,
+                               seed, out_m1, nullptr, nullptr, nullptr, stream);
+}
+
+namespace {
+
+// out[b] = mean over the slots j with cnt2[b,j] > 0 of table[b*k1+j]  (table = the [B,k1,D] per-slot means)
+hipError_t slot_mean(const void* table, const int32_t* cnt2, int x_dtype, int64_t D, int64_t B, int32_t k1,
+                     void* out, hipStream_t stream) {
+    const void* rows[2] = {table, out};
+    fsa::FwdArgs a{};
+    a.x = table; a.x_kind = x_dtype; a.D = D; a.B = B; a.k1 = k1; a.hops = 1;
+    a.slot_cnt = cnt2; a.out = out;
+    a.geom = row_geometry(D, elem_bytes(x_dtype), rows, 2);
+    return fsa::launch_forward(a, stream);
+}
+
+}  // namespace
+
+int fsa_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* indices,
+                         int64_t num_nodes, const void* x, int x_dtype, int64_t D,
+                         const int32_t* seeds, int64_t B, const int32_t* fanouts, uint64_t seed,
+                         void* out, void* out_h1, void* out_h2, void* out_m1,
+                         int32_t* out_ids1, int32_t* out_ids2, int32_t* out_ids3, int32_t* out_cnt2,
+                         void* stream) {
+    if (!indptr || !indices || !x || !fanouts) return FSA_ERR_NULL;
+    if (B != 0 && (!seeds || !out || !out_h1 || !out_m1 || !out_ids1 || !out_cnt2)) return FSA_ERR_NULL;
+    if (indptr_type != FSA_I32 && indptr_type != FSA_I64) return FSA_ERR_DTYPE;
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    const int32_t k1 = fanouts[0], k2 = fanouts[1], k3 = fanouts[2];
+    if (!fanout_ok(k1) || !fanout_ok(k2) || !fanout_ok(k3)) return FSA_ERR_ARG;
+    if (B * k1 > (int64_t)INT32_MAX) return FSA_ERR_ARG;       // hop-1 slots are the roots of the inner call
+    const int eb = elem_bytes(x_dtype);
+    if (!aligned(indptr, indptr_type == FSA_I64 ? 8 : 4) || !aligned(indices, 4) || !aligned(seeds, 4) ||
+        !aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(out_h2, eb) || !aligned(out_m1, eb) ||
+        !aligned(out_ids1, 4) || !aligned(out_ids2, 4) || !aligned(out_ids3, 4) || !aligned(out_cnt2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // hop 0: the seeds' rows -> ids1 and the plain hop-1 mean
+    {
+        const void* rows[2] = {x, out_m1};
+        fsa::FwdArgs a{};
+        a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
+        a.x = x; a.x_kind = x_dtype; a.D = D; a.seeds = seeds; a.B = B; a.k1 = k1; a.hops = 1; a.seed = seed;
+        a.out = out_m1; a.out_ids1 = out_ids1;
+        a.geom = row_geometry(D, eb, rows, 2);
+        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    // hops 1 and 2: the fused two-hop kernel with the B*k1 hop-1 slots as its roots
+    {
+        const void* rows[3] = {x, out_h1, out_h2};
+        fsa::FwdArgs a{};
+        a.indptr = indptr; a.indptr_is64 = indptr_type == FSA_I64; a.indices = indices;
+        a.x = x; a.x_kind = x_dtype; a.D = D; a.seeds = out_ids1; a.B = B * k1; a.k1 = k2; a.k2 = k3; a.hops = 2;
+        a.seed = seed; a.hop_base = 1;
+        a.out = out_h1; a.out_h1 = out_h2; a.out_ids1 = out_ids2; a.out_ids2 = out_ids3; a.out_live = out_cnt2;
+        a.geom = row_geometry(D, eb, rows, 3);
+        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    return slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
+                         const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                         int64_t B, int32_t k1, int32_t k2, int32_t k3,
+                         void* out, void* out_h1, void* out_h2, void* out_m1, int32_t* out_cnt2,
+                         void* stream) {
+    if (!x) return FSA_ERR_NULL;
+    if (B != 0 && (!ids1 || !ids2 || !ids3 || !out || !out_h1 || !out_cnt2)) return FSA_ERR_NULL;
+    if (int rc = check_common(x_dtype, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || !fanout_ok(k2) || !fanout_ok(k3)) return FSA_ERR_ARG;
+    if (B * k1 > (int64_t)INT32_MAX) return FSA_ERR_ARG;
+    const int eb = elem_bytes(x_dtype);
+    if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(out_h2, eb) || !aligned(out_m1, eb) ||
+        !aligned(ids1, 4) || !aligned(ids2, 4) || !aligned(ids3, 4) || !aligned(out_cnt2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (out_m1) {
+        const void* rows[2] = {x, out_m1};
+        fsa::FwdArgs a{};
+        a.x = x; a.x_kind = x_dtype; a.D = D; a.B = B; a.k1 = k1; a.hops = 1; a.ids1 = ids1; a.out = out_m1;
+        a.geom = row_geometry(D, eb, rows, 2);
+        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    {
+        const void* rows[3] = {x, out_h1, out_h2};
+        fsa::FwdArgs a{};
+        a.x = x; a.x_kind = x_dtype; a.D = D; a.seeds = ids1;      // a negative ids1 switches its slot off
+        a.B = B * k1; a.k1 = k2; a.k2 = k3; a.hops = 2; a.ids1 = ids2; a.ids2 = ids3;
+        a.out = out_h1; a.out_h1 = out_h2; a.out_live = out_cnt2;
+        a.geom = row_geometry(D, eb, rows, 3);
+        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    return slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+}
+
+int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                  const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                  int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                  float* grad_x, int64_t num_nodes, float* work, void* stream) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1 || !ids2 || !ids3 || !work)) return FSA_ERR_NULL;
+    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || !fanout_ok(k2) || !fanout_ok(k3)) return FSA_ERR_ARG;
+    if (B * k1 > (int64_t)INT32_MAX) return FSA_ERR_ARG;
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_h2, 4) || !aligned(grad_m1, 4) ||
+        !aligned(grad_x, 4) || !aligned(work, 4) || !aligned(ids1, 4) || !aligned(ids2, 4) || !aligned(ids3, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fsa::launch_deep_grad(grad_out, grad_h1, ids1, ids2, ids3, work, B, k1, k2, k3, D, st) != hipSuccess)
+        return FSA_ERR_HIP;
+    {
+        fsa::BwdArgs a{};
+        a.grad_out = work; a.grad_h1 = grad_h2; a.ids1 = ids2; a.ids2 = ids3; a.root_valid = ids1;
+        a.B = B * k1; a.k1 = k2; a.k2 = k3; a.D = D; a.grad_x = grad_x;
+        if (fsa::launch_backward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    if (grad_m1) {
+        fsa::BwdArgs a{};
+        a.grad_out = grad_m1; a.ids1 = ids1; a.B = B; a.k1 = k1; a.k2 = 0; a.D = D; a.grad_x = grad_x;
+        if (fsa::launch_backward(a, st) != hipSuccess) return FSA_ERR_HIP;
+    }
+    return FSA_OK;
+}
+
+
 const char* fsa_status_string(int status) {
     switch (status) {
         case FSA_OK:        return "ok";

@@ -19,6 +19,7 @@ namespace fsa {
 struct BwdParams {
     const void* grad_out; const void* grad_h1; const int32_t* ids1; const int32_t* ids2;
     void* grad_x; int64_t B; int64_t D; int k1, k2;
+    const int32_t* root_valid;           // 2-hop, nullable: [B], a negative entry switches root b off
 };
 
 // ---------------------------------------------------------------------------------------
@@ -283,6 +284,7 @@ __global__ __launch_bounds__(512) void bwd2_kernel(const BwdParams p) {
     int* uniq = cnt2 + nq_max;
     int* live_slots = smem + nw * per_wave;
 
+    if (p.root_valid && p.root_valid[b] < 0) return;    // workgroup-uniform, before any barrier
     const int u_mine = lane < k1 ? p.ids1[b * k1 + lane] : -1;
     const int nq = wave < k1 ? (k1 - wave + nw - 1) / nw : 0;
     const int spw = kWave / k2;
@@ -354,6 +356,54 @@ __global__ __launch_bounds__(512) void bwd2_kernel(const BwdParams p) {
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Three-hop backward, first step: the gradient that reaches each hop-1 slot's nested mean.
+//   work[b,j,:] = (slot j took part ? grad_out[b,:] / c_b : 0) + grad_h1[b,j,:]
+// where slot j took part iff ids1[b,j] >= 0 and some i has ids2[b,j,i] >= 0 and a non-negative
+// ids3[b,j,i,:], and c_b counts such slots.
+// One wave per root; the two-hop backward then runs over the B*k1 slots as its roots.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void deep_grad_kernel(const float* __restrict__ grad_out,
+                                                        const float* __restrict__ grad_h1,
+                                                        const int32_t* __restrict__ ids1,
+                                                        const int32_t* __restrict__ ids2,
+                                                        const int32_t* __restrict__ ids3, float* __restrict__ work,
+                                                        int64_t B, int k1, int k2, int k3, int64_t D) {
+    const int lane = threadIdx.x & 63;
+    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    if (b >= B) return;                                              // wave-uniform
+    uint64_t part = 0;                                               // bit j: slot j took part
+    const int per_slot = k2 * k3;
+    for (int j = 0; j < k1; ++j) {
+        if (ids1[b * k1 + j] < 0) continue;                          // wave-uniform
+        const int32_t* q2 = ids2 + (b * k1 + j) * (int64_t)k2;
+        const int32_t* q3 = ids3 + (b * k1 + j) * (int64_t)per_slot;
+        bool any = false;
+        for (int e = lane; e < per_slot; e += kWave) any = any || (q3[e] >= 0 && q2[e / k3] >= 0);
+        if (__ballot(any)) part |= 1ull << j;
+    }
+    const int c = __popcll(part);
+    const float inv = c > 0 ? 1.0f / (float)c : 0.0f;
+    for (int64_t d = lane; d < D; d += kWave) {
+        const float g = grad_out[b * D + d] * inv;
+        for (int j = 0; j < k1; ++j) {
+            float v = ((part >> j) & 1ull) ? g : 0.0f;
+            if (grad_h1) v += grad_h1[(b * k1 + j) * D + d];
+            work[(b * k1 + j) * D + d] = v;
+        }
+    }
+}
+
+hipError_t launch_deep_grad(const float* grad_out, const float* grad_h1, const int32_t* ids1, const int32_t* ids2,
+                            const int32_t* ids3, float* work, int64_t B, int k1, int k2, int k3, int64_t D,
+                            hipStream_t stream) {
+    const int wpb = 4;
+    const unsigned grid = (unsigned)((B + wpb - 1) / wpb);
+    hipLaunchKernelGGL(deep_grad_kernel, dim3(grid), dim3(wpb * kWave), 0, stream, grad_out, grad_h1, ids1, ids2, ids3,
+                       work, B, k1, k2, k3, D);
+    return hipGetLastError();
+}
+
 static int env_int(const char* name, int fallback) {
     const char* v = std::getenv(name);
     return v ? std::atoi(v) : fallback;
@@ -389,7 +439,7 @@ static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hi
 hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
     BwdParams p;
     p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
-    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
+    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2; p.root_valid = a.root_valid;
     // kinds: 0 fp32, 1 bfloat16, 2 fp16.  A 16-bit grad_x takes gradients of its own type or fp32.
     switch (a.grad_kind * 3 + a.grad_x_kind) {
         case 0 * 3 + 0: return launch_backward_typed<g_f32, g_f32>(a, p, stream);

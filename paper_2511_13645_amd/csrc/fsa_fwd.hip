@@ -41,6 +41,9 @@ struct FwdParams {
     char* out; char* out_h1; int32_t* out_ids1; int32_t* out_ids2;
     int64_t B; int64_t row_bytes; uint64_t seed;
     int k1, k2, chunks, sub, sub_shift, indptr_is64;
+    uint32_t hop_base;                      // hop counter of the seeds' own rows (0 unless chained)
+    int32_t* out_live;                      // 2-hop, nullable: [B] hop-1 slots that took part
+    const int32_t* slot_cnt;                // slot-mean kernel only: [B,k1] counts, > 0 = takes part
 #ifdef FSA_TRACE
     long long* trace;                       // debug builds: [B][8] wall-clock stamps (10 ns units)
 #endif
@@ -71,33 +74,28 @@ __device__ __forceinline__ void row_extent(const FwdParams& p, int64_t i, int64_
 template <bool REPLAY>
 __device__ __forceinline__ int hop0_id(const FwdParams& p, int64_t b, int lane) {
     if constexpr (REPLAY) {
+        // chained calls pass the level above as `seeds`: a negative entry switches the root off
+        if (p.seeds && p.seeds[b] < 0) return -1;
         return lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
     } else {
+        // a negative seed (an unused slot of the level above, when calls are chained) is an
+        // empty row: nothing is read for it
         const int64_t r = p.seeds[b];
         int64_t s, deg;
-        row_extent(p, r, s, deg);
-        const int64_t pos = floyd_position(p.seed, (uint32_t)r, 0u, p.k1, lane, 0, deg,
+        row_extent(p, r >= 0 ? r : 0, s, deg);
+        if (r < 0) deg = 0;
+        const int64_t pos = floyd_position(p.seed, (uint32_t)r, p.hop_base, p.k1, lane, 0, deg,
                                            lane < p.k1, lane);
         return pos >= 0 ? p.indices[s + pos] : -1;
     }
 }
 
-// ---------------------------------------------------------------------------------------
-// 1-hop: wave per seed
-// ---------------------------------------------------------------------------------------
-template <typename XT, int VB, bool REPLAY>
-__global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
+// One wave: mean of the rows of p.x named by the lanes' non-negative `id`s, in lane order,
+// written to `dst`.  `ids` is the wave's LDS strip of 64 ints.
+template <typename XT, int VB>
+__device__ __forceinline__ void wave_mean_of_rows(const FwdParams& p, int id, int* ids, int lane, char* dst) {
     using C = Chunk<XT, VB>;
     constexpr int VE = C::VE;
-    extern __shared__ int smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (b >= p.B) return;                       // wave-uniform; no block barrier below
-    int* ids = smem + wave * kWave;
-
-    int id = hop0_id<REPLAY>(p, b, lane);
-    if (!REPLAY && p.out_ids1 && lane < p.k1) p.out_ids1[b * p.k1 + lane] = id;
     // stage the valid IDs, in slot order, in this wave's LDS strip
     const uint64_t valid = __ballot(id >= 0);
     const int cnt = __popcll(valid);
@@ -125,9 +123,39 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
         if (sg == 0 && live) {
 #pragma unroll
             for (int e = 0; e < VE; ++e) acc[e] *= inv_cnt;
-            *reinterpret_cast<typename C::Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(acc);
+            *reinterpret_cast<typename C::Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc);
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// 1-hop: wave per seed
+// ---------------------------------------------------------------------------------------
+template <typename XT, int VB, bool REPLAY>
+__global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
+    extern __shared__ int smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (b >= p.B) return;                       // wave-uniform; no block barrier below
+    int* ids = smem + wave * kWave;
+
+    int id = hop0_id<REPLAY>(p, b, lane);
+    if (!REPLAY && p.out_ids1 && lane < p.k1) p.out_ids1[b * p.k1 + lane] = id;
+    wave_mean_of_rows<XT, VB>(p, id, ids, lane, p.out + b * p.row_bytes);
+}
+
+// Mean over the hop-1 slots that took part of the per-slot rows of a [B,k1,D] table (the last
+// step of a chained, deeper-hop call): lane j names row b*k1+j when slot_cnt[b,j] > 0.
+template <typename XT, int VB>
+__global__ __launch_bounds__(256) void slot_mean_kernel(const FwdParams p) {
+    extern __shared__ int smem[];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
+    if (b >= p.B) return;                       // wave-uniform; no block barrier below
+    const int id = (lane < p.k1 && p.slot_cnt[b * p.k1 + lane] > 0) ? (int)(b * p.k1 + lane) : -1;
+    wave_mean_of_rows<XT, VB>(p, id, smem + wave * kWave, lane, p.out + b * p.row_bytes);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -284,7 +312,7 @@ void fwd2_kernel(const FwdParams p) {
                     const int64_t s = (int64_t)(((uint64_t)s_hi << 32) | s_lo);
                     const int64_t deg = (int64_t)__shfl(deg_own, src);
                     const int off = __shfl(off_own, src);
-                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, 1u, k2, li, valid ? g * k2 : 0,
+                    const int64_t pos = floyd_position(p.seed, (uint32_t)u, p.hop_base + 1u, k2, li, valid ? g * k2 : 0,
                                                        deg, active, lane);
                     if (pos >= 0) {
                         idv[t] = p.indices[s + pos];
@@ -377,6 +405,7 @@ void fwd2_kernel(const FwdParams p) {
         }
         FSA_STAMP(5);
         if (nw == 1) {
+            if (c0 == 0 && lane == 0 && p.out_live) p.out_live[b] = live_slots[0];
             if (sg == 0 && live) {
                 const int c1 = live_slots[0];
                 const float inv1 = inv_count(c1 > 0 ? c1 : 1);
@@ -394,6 +423,7 @@ void fwd2_kernel(const FwdParams p) {
         if (wave == 0 && sg == 0 && live) {
             int c1 = 0;
             for (int w = 0; w < nw; ++w) c1 += live_slots[w];
+            if (c0 == 0 && sl == 0 && p.out_live) p.out_live[b] = c1;
             float tot[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e) tot[e] = 0.0f;
@@ -434,6 +464,12 @@ template <typename XT, int VB>
 static hipError_t launch_typed(const FwdArgs& a, const FwdParams& p, hipStream_t stream) {
     constexpr int VE = Chunk<XT, VB>::VE;
     const bool replay = a.indptr == nullptr;
+    if (a.slot_cnt) {                           // mean over the per-slot rows of a [B,k1,D] table
+        const int wpb = 4;
+        const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
+        hipLaunchKernelGGL((slot_mean_kernel<XT, VB>), dim3(grid), dim3(wpb * kWave), sizeof(int) * kWave * wpb, stream, p);
+        return hipGetLastError();
+    }
     if (a.hops == 1) {
         static const int wpb = [] { int v = env_int("FSA_FWD1_WAVES", 4); return v >= 1 && v <= 4 ? v : 4; }();
         const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
@@ -460,6 +496,7 @@ hipError_t launch_forward(const FwdArgs& a, hipStream_t stream) {
     p.B = a.B; p.row_bytes = a.D * (a.x_kind == 0 ? 4 : 2); p.seed = a.seed;
     p.k1 = a.k1; p.k2 = a.k2; p.chunks = a.geom.chunks; p.sub = a.geom.sub;
     p.sub_shift = __builtin_ctz((unsigned)a.geom.sub); p.indptr_is64 = a.indptr_is64;
+    p.hop_base = a.hop_base; p.out_live = a.out_live; p.slot_cnt = a.slot_cnt;
 #ifdef FSA_TRACE
     { const char* t = std::getenv("FSA_TRACE_PTR"); p.trace = t ? reinterpret_cast<long long*>(std::strtoull(t, nullptr, 16)) : nullptr; }
 #endif

@@ -21,6 +21,11 @@ struct FwdArgs {
     const int32_t* ids1; const int32_t* ids2;   // replay inputs (indptr == nullptr selects replay)
     void* out; void* out_h1; int32_t* out_ids1; int32_t* out_ids2;
     RowGeom geom;
+    // chained (deeper-hop) calls
+    uint32_t hop_base = 0;                      // hop counter of the seeds' own rows; negative seeds = empty rows
+    int32_t* out_live = nullptr;                // 2-hop: [B] number of hop-1 slots that took part
+    const int32_t* slot_cnt = nullptr;          // non-null selects the slot-mean kernel: out[b] = mean of the
+                                                // rows x[b*k1+j] with slot_cnt[b,j] > 0
 };
 
 struct BwdArgs {
@@ -28,6 +33,7 @@ struct BwdArgs {
     int64_t B; int k1; int k2; int64_t D; void* grad_x;
     int grad_kind = 0;      // element type of grad_out / grad_h1: 0 fp32, 1 bfloat16, 2 fp16
     int grad_x_kind = 0;    // element type of grad_x
+    const int32_t* root_valid = nullptr;   // 2-hop, chained calls: [B], a negative entry switches root b off
 };
 
 // Weighted mean: the same launches with per-edge weights (edge_w aligned with indices) and
@@ -42,5 +48,9 @@ hipError_t launch_forward(const FwdArgs& a, hipStream_t stream);
 hipError_t launch_forward_weighted(const FwdArgs& a, const WeightArgs& w, hipStream_t stream);
 hipError_t launch_backward_weighted(const BwdArgs& a, const WeightArgs& w, hipStream_t stream);
 hipError_t launch_backward(const BwdArgs& a, hipStream_t stream);
+// work[b,j,:] = (slot j took part ? grad_out[b,:] / #such slots : 0) + grad_h1[b,j,:]  (grad_h1 nullable)
+hipError_t launch_deep_grad(const float* grad_out, const float* grad_h1, const int32_t* ids1, const int32_t* ids2,
+                            const int32_t* ids3, float* work, int64_t B, int k1, int k2, int k3, int64_t D,
+                            hipStream_t stream);
 
 }  // namespace fsa

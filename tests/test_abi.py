@@ -115,6 +115,53 @@ def test_reduced_precision_backward_rejects_bad_arguments(fsa):
         assert bw(gt=gt, xt=xt, B=0) == 0
 
 
+def test_layerwise_and_three_hop_entry_points_reject_bad_arguments(fsa):
+    L = fsa.lib()
+    fan = (ctypes.c_int32 * 3)(5, 3, 2)
+    fp = ctypes.cast(fan, ctypes.c_void_p)
+
+    def lw(**k):
+        a = dict(indptr=FAKE, itype=0, indices=FAKE, n=100, x=FAKE, xt=0, D=16, seeds=FAKE, B=8, fan=fp, seed=1,
+                 out=FAKE, h1=FAKE, m1=FAKE, i1=FAKE, i2=FAKE, s=None)
+        a.update(k)
+        return L.fsa_sample_mean_layerwise_fwd(*[a[n] for n in ("indptr", "itype", "indices", "n", "x", "xt", "D", "seeds", "B",
+                                                                "fan", "seed", "out", "h1", "m1", "i1", "i2", "s")])
+    assert lw(m1=None) == -1 and lw(x=None) == -1 and lw(xt=9) == -3 and lw(m1=FAKE + 2) == -4 and lw(D=0) == -2
+    assert lw(B=0) == 0
+
+    def f3(**k):
+        a = dict(indptr=FAKE, itype=0, indices=FAKE, n=100, x=FAKE, xt=0, D=16, seeds=FAKE, B=8, fan=fp, seed=1,
+                 out=FAKE, h1=FAKE, h2=FAKE, m1=FAKE, i1=FAKE, i2=FAKE, i3=FAKE, c2=FAKE, s=None)
+        a.update(k)
+        return L.fsa_sample_mean3_fwd(*[a[n] for n in ("indptr", "itype", "indices", "n", "x", "xt", "D", "seeds", "B", "fan",
+                                                       "seed", "out", "h1", "h2", "m1", "i1", "i2", "i3", "c2", "s")])
+    for name in ("indptr", "indices", "x", "seeds", "fan", "out", "h1", "m1", "i1", "c2"):
+        assert f3(**{name: None}) == -1, name
+    assert f3(xt=4) == -3 and f3(itype=2) == -3 and f3(D=0) == -2 and f3(B=-1) == -2
+    assert f3(fan=ctypes.cast((ctypes.c_int32 * 3)(5, 0, 2), ctypes.c_void_p)) == -2
+    assert f3(fan=ctypes.cast((ctypes.c_int32 * 3)(64, 3, 2), ctypes.c_void_p), B=2**26) == -2   # B*k1 beyond 2^31-1
+    assert f3(c2=FAKE + 2) == -4 and f3(h2=FAKE + 1, xt=1) == -4
+    assert f3(B=0) == 0 and f3(B=0, h2=None, i2=None, i3=None) == 0
+
+    def r3(**k):
+        a = dict(x=FAKE, xt=0, D=8, n=10, i1=FAKE, i2=FAKE, i3=FAKE, B=4, k1=3, k2=2, k3=2, out=FAKE, h1=FAKE, h2=FAKE,
+                 m1=FAKE, c2=FAKE, s=None)
+        a.update(k)
+        return L.fsa_mean3_replay_fwd(*[a[n] for n in ("x", "xt", "D", "n", "i1", "i2", "i3", "B", "k1", "k2", "k3", "out", "h1",
+                                                       "h2", "m1", "c2", "s")])
+    assert r3(x=None) == -1 and r3(i3=None) == -1 and r3(h1=None) == -1 and r3(c2=None) == -1
+    assert r3(k3=0) == -2 and r3(k1=65) == -2 and r3(xt=3) == -3 and r3(out=FAKE + 2) == -4 and r3(B=0) == 0
+
+    def b3(**k):
+        a = dict(go=FAKE, g1=FAKE, g2=FAKE, gm=FAKE, i1=FAKE, i2=FAKE, i3=FAKE, B=4, k1=3, k2=2, k3=2, D=8, gx=FAKE, n=10,
+                 w=FAKE, s=None)
+        a.update(k)
+        return L.fsa_mean3_bwd(*[a[n] for n in ("go", "g1", "g2", "gm", "i1", "i2", "i3", "B", "k1", "k2", "k3", "D", "gx", "n",
+                                                "w", "s")])
+    assert b3(go=None) == -1 and b3(gx=None) == -1 and b3(w=None) == -1 and b3(i2=None) == -1
+    assert b3(k2=0) == -2 and b3(D=0) == -2 and b3(w=FAKE + 2) == -4 and b3(B=0) == 0 and b3(B=0, w=None) == 0
+
+
 def test_binding_fails_loudly_without_library(fsa, monkeypatch):
     monkeypatch.setattr(fsa, "_lib", None)
     monkeypatch.setattr(fsa, "LIB_PATH", "/nonexistent/libfsa_hip.so")
