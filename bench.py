@@ -76,6 +76,129 @@ def load_or_make_workload(name, scale, cache, dev):
     return w
 
 
+def three_hop(args, L, binding, synth, torch, w, B, dev) -> int:
+    """One step = fsa_sample_mean3_fwd (one-hop kernel, fused two-hop kernel over the B*k1 hop-1
+    slots, slot mean) on a fresh seed batch, IDs of all three levels emitted."""
+    g, x = w.graph, w.x
+    k1, k2 = w.fanouts
+    k3 = args.three_hop
+    N, D = x.shape
+    elem, iptr = x.element_size(), g.indptr.element_size()
+    steps, warmup = args.steps, args.warmup
+    emit = not args.no_emit
+    seeds = synth.seed_batches(N, B, steps + warmup, seed=2).to(dev)
+    out = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_m1 = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev)
+    cnt2 = torch.empty((B, k1), dtype=torch.int32, device=dev)
+    ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev)
+    ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev)
+    ids3 = torch.empty((B, k1, k2, k3), dtype=torch.int32, device=dev)
+    fan_host = (ctypes.c_int32 * 3)(k1, k2, k3)
+    stream = torch.cuda.current_stream().cuda_stream
+    x_code = {torch.float32: binding.FSA_F32, torch.bfloat16: binding.FSA_BF16, torch.float16: binding.FSA_F16}[x.dtype]
+
+    def step(i, with_ids):
+        rc = L.fsa_sample_mean3_fwd(g.indptr.data_ptr(), binding.FSA_I64 if iptr == 8 else binding.FSA_I32,
+                                    g.indices.data_ptr(), N, x.data_ptr(), x_code, D, seeds[i].data_ptr(), B,
+                                    ctypes.cast(fan_host, ctypes.c_void_p), w.sampler_seed, out.data_ptr(),
+                                    out_h1.data_ptr(), None, out_m1.data_ptr(), ids1.data_ptr(),
+                                    ids2.data_ptr() if with_ids else None, ids3.data_ptr() if with_ids else None,
+                                    cnt2.data_ptr(), stream)
+        if rc != 0:
+            raise RuntimeError("fsa_sample_mean3_fwd -> %d" % rc)
+    for i in range(warmup):
+        step(i, emit)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_start = time.perf_counter()
+    ev0.record()
+    for i in range(warmup, warmup + steps):
+        step(i, emit)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    step_ms = ev0.elapsed_time(ev1) / steps
+    # rows of a few of the timed batches, counted by untimed emitting calls
+    n_cnt = min(steps, 5)
+    leaf = live2 = live1 = 0
+    for i in range(warmup, warmup + n_cnt):
+        step(i, True)
+        leaf += int((ids3 >= 0).sum().item())
+        live2 += int((ids2 >= 0).sum().item())
+        live1 += int((ids1 >= 0).sum().item())
+    leaf, live2, live1 = leaf / n_cnt, live2 / n_cnt, live1 / n_cnt
+    # bytes the method must move per step: every leaf row once with its `indices` entry; an indptr
+    # pair and an `indices` entry per sampled row owner; the hop-1 rows for out_m1; out_h1 written
+    # and read back once by the slot mean; ids1 / cnt2 written and read back; the other outputs once
+    alg = leaf * (D * elem + 4) + (live2 + live1) * (4 + 2 * iptr) + B * (2 * iptr + 4)
+    alg += live1 * D * elem + 2 * B * D * elem + 2 * B * k1 * D * elem + 4 * 4 * B * k1
+    if emit:
+        alg += 4 * B * k1 * k2 * (1 + k3)
+    achieved = alg / (step_ms * 1e-3) / 1e9
+    log("[bench] three-hop %d/%d/%d: %.1f us/step by events, %.0f leaf rows/step, %.1f MB algorithmic/step" %
+        (k1, k2, k3, step_ms * 1e3, leaf, alg / 1e6))
+    other_paths = None
+    if args.paths:
+        other_paths = {}
+        n_p = min(steps, 20)
+        step(warmup, True)                              # IDs of one batch, reused below
+        torch.cuda.synchronize()
+
+        def timed(fn):
+            fn(); fn()
+            torch.cuda.synchronize()
+            ev0.record()
+            for _ in range(n_p):
+                fn()
+            ev1.record()
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / n_p
+
+        def replay():
+            rc = L.fsa_mean3_replay_fwd(x.data_ptr(), x_code, D, N, ids1.data_ptr(), ids2.data_ptr(), ids3.data_ptr(),
+                                        B, k1, k2, k3, out.data_ptr(), out_h1.data_ptr(), None, out_m1.data_ptr(),
+                                        cnt2.data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError("fsa_mean3_replay_fwd -> %d" % rc)
+        r_ms = timed(replay)
+        rows_b = int((ids3 >= 0).sum().item())
+        other_paths["replay_forward"] = {"launch_us": r_ms * 1e3, "rows_per_s": rows_b / (r_ms * 1e-3)}
+        if x.dtype == torch.float32:
+            g_out = synth.upstream_grad((B, D), seed=3, device=dev)
+            g_h1 = synth.upstream_grad((B, k1, D), seed=4, device=dev)
+            work = torch.empty((B, k1, D), dtype=torch.float32, device=dev)
+            grad_x = torch.zeros((N, D), dtype=torch.float32, device=dev)
+
+            def bwd():
+                rc = L.fsa_mean3_bwd(g_out.data_ptr(), g_h1.data_ptr(), None, None, ids1.data_ptr(), ids2.data_ptr(),
+                                     ids3.data_ptr(), B, k1, k2, k3, D, grad_x.data_ptr(), N, work.data_ptr(), stream)
+                if rc != 0:
+                    raise RuntimeError("fsa_mean3_bwd -> %d" % rc)
+            b_ms = timed(bwd)
+            other_paths["backward"] = {"launch_us": b_ms * 1e3, "rows_per_s": rows_b / (b_ms * 1e-3),
+                                       "atomic_payload_gbps": rows_b * D * 4 / (b_ms * 1e-3) / 1e9}
+        log("[bench] three-hop other paths: %s" % json.dumps(other_paths))
+
+    line = {
+        "metric": "sampled neighbor rows aggregated/sec + achieved HBM GB/s, fanout %d/%d/%d D=%d" % (k1, k2, k3, D),
+        "value": leaf * steps / wall, "unit": "rows/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": wall * 1e3 / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if x.dtype == torch.bfloat16 else "f32", "data": "synthetic",
+        "config": {"workload": "%s three-hop: N=%d, E=%d, D=%d, B=%d, fanouts=[%d, %d, %d], emit_ids=%s" %
+                               (w.name, N, g.num_edges, D, B, k1, k2, k3, emit),
+                   "global_batch": B, "rows_per_launch": leaf, "algorithmic_bytes_per_launch": alg},
+        "hbm_gbps": achieved,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "fwd1_kernel + fwd2_kernel + slot_mean_kernel (one step)", "launch_us": step_ms * 1e3},
+        "cpu_baseline": None,
+        "other_paths": other_paths,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +220,8 @@ def main() -> int:
                     "with and without ID / per-slot emission, on the same graph")
     ap.add_argument("--feature-dtype", default="", choices=["", "f32", "bf16"],
                     help="convert the workload's feature table to this type first (fp32 variant of the headline)")
+    ap.add_argument("--three-hop", type=int, default=0, metavar="K3",
+                    help="time the three-hop forward (workload fanouts + K3) instead of the workload's own path")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
     args = ap.parse_args()
@@ -142,6 +267,11 @@ def main() -> int:
         (w.name, N, g.num_edges, D, str(x.dtype), B, fan, time.time() - t0))
 
     steps, warmup = args.steps, args.warmup
+    if args.three_hop:
+        if hops != 2:
+            print("bench.py: --three-hop needs a two-hop workload", file=sys.stderr)
+            return 2
+        return three_hop(args, L, binding, synth, torch, w, B, dev)
     seeds = synth.seed_batches(N, B, steps + warmup, seed=2).to(dev)
     emit = not args.no_emit
     out = torch.empty((B, D), dtype=x.dtype, device=dev)
