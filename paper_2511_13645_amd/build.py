@@ -12,7 +12,7 @@ SOURCES = ["fsa_api.hip", "fsa_fwd.hip", "fsa_bwd.hip", "fsa_wfwd.hip", "fsa_wbw
 HEADERS = ["fsa_device.hip.h", "fsa_internal.h", os.path.join("..", "..", "include", "fsa.h")]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-munsafe-fp-atomics",
     # keep hipcc from forming packed-fp32 instructions out of scalar float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -28,12 +28,29 @@ def hipcc() -> str:
 
 
 def build_hip(extra_flags=(), verbose: bool = False) -> str:
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-o", tmp, *[os.path.join(CSRC, s) for s in SOURCES]]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, cwd=CSRC)
-    os.replace(tmp, LIB)
+    """Compile every source to an object (side by side, one hipcc each), then link the library."""
+    from concurrent.futures import ThreadPoolExecutor
+    import shutil
+    import tempfile
+    work = tempfile.mkdtemp(prefix="fsa_build_")
+    try:
+        def compile_one(src: str) -> str:
+            obj = os.path.join(work, src + ".o")
+            cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            subprocess.run(cmd, check=True, cwd=CSRC)
+            return obj
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        tmp = LIB + ".tmp.%d" % os.getpid()
+        cmd = [hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", "-o", tmp, *objs]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True, cwd=CSRC)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(work, ignore_errors=True)
     return LIB
 
 

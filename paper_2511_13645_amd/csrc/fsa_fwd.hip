@@ -29,6 +29,9 @@
 #ifndef FSA_PASS_GROUP
 #define FSA_PASS_GROUP 4
 #endif
+#ifndef FSA_MULTI_LOADS
+#define FSA_MULTI_LOADS 8
+#endif
 #ifndef FSA_FWD2_MIN_WAVES_PER_EU
 #define FSA_FWD2_MIN_WAVES_PER_EU 1
 #endif
@@ -175,7 +178,14 @@ __global__ __launch_bounds__(256) void slot_mean_kernel(const FwdParams p) {
 // ---------------------------------------------------------------------------------------
 constexpr int kPassGroup = FSA_PASS_GROUP;
 
-template <typename XT, int VB, bool REPLAY>
+// MT > 0 selects the gather for rows wider than one tile of 64 lanes (2 .. MT tiles, MT at
+// most kMultiTiles): all tiles of a row are loaded back to back, so the cache line that two
+// neighbouring tiles share is fetched once -- walking the whole list once per tile fetched it
+// twice, 20 % more HBM-side traffic than the rows themselves on 2408-byte rows.  MT = 0 is
+// the single-tile gather (and the fallback for rows wider than kMultiTiles tiles).
+constexpr int kMultiTiles = 8;
+
+template <typename XT, int VB, bool REPLAY, int MT>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(FSA_FWD2_MIN_WAVES_PER_EU)))
 void fwd2_kernel(const FwdParams p) {
     using C = Chunk<XT, VB>;
@@ -357,86 +367,184 @@ void fwd2_kernel(const FwdParams p) {
 
     // gather
     FSA_STAMP(4);
-    for (int c0 = 0; c0 < p.chunks; c0 += sub) {
-        const int chunk = c0 + sl;
-        const bool live = chunk < p.chunks;
-        const int64_t chunk_off = (int64_t)chunk * VB;
-        float acc[VE], root[VE];
+    if constexpr (MT > 0) {
+        // rows wider than one tile: sub == 64, one sub-group, the wave walks its whole list
+        constexpr int R = FSA_MULTI_LOADS / MT;                    // rows in flight: 2 x 4 tiles or 1 x 8
+        const int tiles = (p.chunks + kWave - 1) >> 6;             // 2 .. MT, checked on the host
+        float acc[MT][VE], root[MT][VE];
 #pragma unroll
-        for (int e = 0; e < VE; ++e) { acc[e] = 0.0f; root[e] = 0.0f; }
-        if (p.out_h1 && live) {                                    // empty slots get zero rows
-            for (int i = sg; i < n_empty; i += nsg)
-                *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + wave + empty_q[i] * nw) * p.row_bytes + chunk_off) = C::pack(acc);
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) { acc[t][e] = 0.0f; root[t][e] = 0.0f; }
         }
-        // Row loads carry no branch of their own: past the end of the list they re-read its
-        // last row (a cache hit) and lanes beyond the row width re-read chunk 0; the results
-        // are simply not accumulated.  This keeps kUnroll loads in flight per lane.
-        const int64_t load_off = live ? chunk_off : 0;
-        for (int i0 = 0; i0 < my_len; i0 += U) {
-            int2 ent[U];
-            Raw r[U];
+        if (p.out_h1) {                                            // empty slots get zero rows
+            for (int i = 0; i < n_empty; ++i) {
+                char* dst = p.out_h1 + (b * k1 + wave + empty_q[i] * nw) * p.row_bytes;
+                for (int chunk = lane; chunk < p.chunks; chunk += kWave)
+                    *reinterpret_cast<Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc[0]);
+            }
+        }
+        for (int i0 = 0; i0 < total; i0 += R) {
+            int2 ent[R];
+            Raw r[R][MT];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = i0 + u < my_len ? i0 + u : my_len - 1;
-                ent[u] = flat[my_start + i];
+            for (int u = 0; u < R; ++u) {
+                const int i = i0 + u < total ? i0 + u : total - 1;
+                ent[u] = flat[i];
                 const uint64_t row_off = ((uint64_t)((uint32_t)ent[u].y & 0x7fffffffu) << 32) | (uint32_t)ent[u].x;
-                r[u] = *reinterpret_cast<const Raw*>(p.x + row_off + load_off);
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    if (t < tiles) {                               // wave-uniform
+                        const int chunk = t * kWave + lane;        // lanes past the row width re-read chunk 0
+                        r[u][t] = *reinterpret_cast<const Raw*>(p.x + row_off + (chunk < p.chunks ? (int64_t)chunk * VB : 0));
+                    }
+                }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (i0 + u < my_len) {
-                    C::add(acc, r[u]);
+            for (int u = 0; u < R; ++u) {
+                if (i0 + u < total) {
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+                        if (t < tiles) C::add(acc[t], r[u][t]);
                     if (ent[u].y < 0) {                            // last row of its slot
-                        const int meta = flat_meta[my_start + i0 + u];
+                        const int meta = flat_meta[i0 + u];
                         const float inv = inv_count(meta >> 8);
+                        char* dst = p.out_h1 ? p.out_h1 + (b * k1 + (meta & 0xff)) * p.row_bytes : nullptr;
 #pragma unroll
-                        for (int e = 0; e < VE; ++e) { acc[e] *= inv; root[e] += acc[e]; }
-                        if (live && p.out_h1)
-                            *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + (meta & 0xff)) * p.row_bytes + chunk_off) = C::pack(acc);
+                        for (int t = 0; t < MT; ++t) {
+                            if (t < tiles) {
+                                const int chunk = t * kWave + lane;
 #pragma unroll
-                        for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
+                                for (int e = 0; e < VE; ++e) { acc[t][e] *= inv; root[t][e] += acc[t][e]; }
+                                if (dst && chunk < p.chunks)
+                                    *reinterpret_cast<Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc[t]);
+#pragma unroll
+                                for (int e = 0; e < VE; ++e) acc[t][e] = 0.0f;
+                            }
+                        }
                     }
                 }
             }
         }
-        for (int off = sub; off < kWave; off <<= 1) {
-#pragma unroll
-            for (int e = 0; e < VE; ++e) root[e] += __shfl_xor(root[e], off);
-        }
         FSA_STAMP(5);
-        if (nw == 1) {
-            if (c0 == 0 && lane == 0 && p.out_live) p.out_live[b] = live_slots[0];
-            if (sg == 0 && live) {
-                const int c1 = live_slots[0];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (t < tiles) {                                       // workgroup-uniform
+                const int chunk = t * kWave + lane;
+                const bool live = chunk < p.chunks;
+                if (nw == 1) {
+                    const int c1 = live_slots[0];
+                    if (t == 0 && lane == 0 && p.out_live) p.out_live[b] = c1;
+                    const float inv1 = inv_count(c1 > 0 ? c1 : 1);
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) root[t][e] *= inv1;
+                    if (live) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(root[t]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) red[(wave * kWave + lane) * VE + e] = root[t][e];
+                    __syncthreads();
+                    if (wave == 0) {
+                        int c1 = 0;
+                        for (int w = 0; w < nw; ++w) c1 += live_slots[w];
+                        if (t == 0 && lane == 0 && p.out_live) p.out_live[b] = c1;
+                        float tot[VE];
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) tot[e] = 0.0f;
+                        for (int w = 0; w < nw; ++w) {
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) tot[e] += red[(w * kWave + lane) * VE + e];
+                        }
+                        const float inv1 = inv_count(c1 > 0 ? c1 : 1);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) tot[e] *= inv1;
+                        if (live) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(tot);
+                    }
+                    __syncthreads();                               // red is reused by the next tile
+                }
+            }
+        }
+    } else {
+        for (int c0 = 0; c0 < p.chunks; c0 += sub) {
+            const int chunk = c0 + sl;
+            const bool live = chunk < p.chunks;
+            const int64_t chunk_off = (int64_t)chunk * VB;
+            float acc[VE], root[VE];
+    #pragma unroll
+            for (int e = 0; e < VE; ++e) { acc[e] = 0.0f; root[e] = 0.0f; }
+            if (p.out_h1 && live) {                                    // empty slots get zero rows
+                for (int i = sg; i < n_empty; i += nsg)
+                    *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + wave + empty_q[i] * nw) * p.row_bytes + chunk_off) = C::pack(acc);
+            }
+            // Row loads carry no branch of their own: past the end of the list they re-read its
+            // last row (a cache hit) and lanes beyond the row width re-read chunk 0; the results
+            // are simply not accumulated.  This keeps kUnroll loads in flight per lane.
+            const int64_t load_off = live ? chunk_off : 0;
+            for (int i0 = 0; i0 < my_len; i0 += U) {
+                int2 ent[U];
+                Raw r[U];
+    #pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u < my_len ? i0 + u : my_len - 1;
+                    ent[u] = flat[my_start + i];
+                    const uint64_t row_off = ((uint64_t)((uint32_t)ent[u].y & 0x7fffffffu) << 32) | (uint32_t)ent[u].x;
+                    r[u] = *reinterpret_cast<const Raw*>(p.x + row_off + load_off);
+                }
+    #pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (i0 + u < my_len) {
+                        C::add(acc, r[u]);
+                        if (ent[u].y < 0) {                            // last row of its slot
+                            const int meta = flat_meta[my_start + i0 + u];
+                            const float inv = inv_count(meta >> 8);
+    #pragma unroll
+                            for (int e = 0; e < VE; ++e) { acc[e] *= inv; root[e] += acc[e]; }
+                            if (live && p.out_h1)
+                                *reinterpret_cast<Raw*>(p.out_h1 + (b * k1 + (meta & 0xff)) * p.row_bytes + chunk_off) = C::pack(acc);
+    #pragma unroll
+                            for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
+                        }
+                    }
+                }
+            }
+            for (int off = sub; off < kWave; off <<= 1) {
+    #pragma unroll
+                for (int e = 0; e < VE; ++e) root[e] += __shfl_xor(root[e], off);
+            }
+            FSA_STAMP(5);
+            if (nw == 1) {
+                if (c0 == 0 && lane == 0 && p.out_live) p.out_live[b] = live_slots[0];
+                if (sg == 0 && live) {
+                    const int c1 = live_slots[0];
+                    const float inv1 = inv_count(c1 > 0 ? c1 : 1);
+    #pragma unroll
+                    for (int e = 0; e < VE; ++e) root[e] *= inv1;
+                    *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(root);
+                }
+                continue;
+            }
+            if (sg == 0) {
+    #pragma unroll
+                for (int e = 0; e < VE; ++e) red[(wave * sub + sl) * VE + e] = root[e];
+            }
+            __syncthreads();
+            if (wave == 0 && sg == 0 && live) {
+                int c1 = 0;
+                for (int w = 0; w < nw; ++w) c1 += live_slots[w];
+                if (c0 == 0 && sl == 0 && p.out_live) p.out_live[b] = c1;
+                float tot[VE];
+    #pragma unroll
+                for (int e = 0; e < VE; ++e) tot[e] = 0.0f;
+                for (int w = 0; w < nw; ++w) {
+    #pragma unroll
+                    for (int e = 0; e < VE; ++e) tot[e] += red[(w * sub + sl) * VE + e];
+                }
                 const float inv1 = inv_count(c1 > 0 ? c1 : 1);
-#pragma unroll
-                for (int e = 0; e < VE; ++e) root[e] *= inv1;
-                *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(root);
+    #pragma unroll
+                for (int e = 0; e < VE; ++e) tot[e] *= inv1;
+                *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(tot);
             }
-            continue;
+            if (c0 + sub < p.chunks) __syncthreads();       // red is reused by the next tile
         }
-        if (sg == 0) {
-#pragma unroll
-            for (int e = 0; e < VE; ++e) red[(wave * sub + sl) * VE + e] = root[e];
-        }
-        __syncthreads();
-        if (wave == 0 && sg == 0 && live) {
-            int c1 = 0;
-            for (int w = 0; w < nw; ++w) c1 += live_slots[w];
-            if (c0 == 0 && sl == 0 && p.out_live) p.out_live[b] = c1;
-            float tot[VE];
-#pragma unroll
-            for (int e = 0; e < VE; ++e) tot[e] = 0.0f;
-            for (int w = 0; w < nw; ++w) {
-#pragma unroll
-                for (int e = 0; e < VE; ++e) tot[e] += red[(w * sub + sl) * VE + e];
-            }
-            const float inv1 = inv_count(c1 > 0 ? c1 : 1);
-#pragma unroll
-            for (int e = 0; e < VE; ++e) tot[e] *= inv1;
-            *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(tot);
-        }
-        if (c0 + sub < p.chunks) __syncthreads();       // red is reused by the next tile
     }
 }
 
@@ -481,8 +589,17 @@ static hipError_t launch_typed(const FwdArgs& a, const FwdParams& p, hipStream_t
         const int nq_max = (a.k1 + nw - 1) / nw;
         const size_t lds = sizeof(int) * ((size_t)nw * (4 * nq_max * a.k2 + 2 * nq_max) + nw)
                          + sizeof(float) * (size_t)nw * a.geom.sub * VE;
-        if (replay) hipLaunchKernelGGL((fwd2_kernel<XT, VB, true>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
-        else        hipLaunchKernelGGL((fwd2_kernel<XT, VB, false>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
+        const dim3 grid((unsigned)a.B), block(nw * kWave);
+        const int tiles = a.geom.tiles;
+#define FSA_LAUNCH_FWD2(MT_)                                                                                   \
+        do {                                                                                                   \
+            if (replay) hipLaunchKernelGGL((fwd2_kernel<XT, VB, true, MT_>), grid, block, lds, stream, p);     \
+            else        hipLaunchKernelGGL((fwd2_kernel<XT, VB, false, MT_>), grid, block, lds, stream, p);    \
+        } while (0)
+        if (tiles <= 1 || tiles > kMultiTiles) FSA_LAUNCH_FWD2(0);
+        else if (tiles <= 4) FSA_LAUNCH_FWD2(4);
+        else FSA_LAUNCH_FWD2(8);
+#undef FSA_LAUNCH_FWD2
     }
     return hipGetLastError();
 }
