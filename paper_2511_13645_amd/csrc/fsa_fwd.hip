@@ -95,7 +95,7 @@ __device__ __forceinline__ int hop0_id(const FwdParams& p, int64_t b, int lane) 
 
 // One wave: mean of the rows of p.x named by the lanes' non-negative `id`s, in lane order,
 // written to `dst`.  `ids` is the wave's LDS strip of 64 ints.
-template <typename XT, int VB>
+template <typename XT, int VB, int MT>
 __device__ __forceinline__ void wave_mean_of_rows(const FwdParams& p, int id, int* ids, int lane, char* dst) {
     using C = Chunk<XT, VB>;
     constexpr int VE = C::VE;
@@ -104,6 +104,53 @@ __device__ __forceinline__ void wave_mean_of_rows(const FwdParams& p, int id, in
     const int cnt = __popcll(valid);
     if (id >= 0) ids[__popcll(valid & lanemask_lt(lane))] = id;
     __builtin_amdgcn_wave_barrier();
+
+    if constexpr (MT > 0) {
+        // rows of 2 .. MT tiles of 64 lanes: all tiles of a row are loaded back to back, so a
+        // cache line shared by neighbouring tiles is fetched once
+        using Raw = typename C::Raw;
+        constexpr int R = FSA_MULTI_LOADS / MT;                    // rows in flight
+        const int tiles = (p.chunks + kWave - 1) >> 6;
+        const float inv = inv_count(cnt > 0 ? cnt : 1);
+        float acc[MT][VE];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[t][e] = 0.0f;
+        }
+        for (int i0 = 0; i0 < cnt; i0 += R) {
+            Raw r[R][MT];
+#pragma unroll
+            for (int u = 0; u < R; ++u) {
+                const int64_t row_off = (int64_t)ids[i0 + u < cnt ? i0 + u : cnt - 1] * p.row_bytes;
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    if (t < tiles) {                               // wave-uniform
+                        const int chunk = t * kWave + lane;        // lanes past the row width re-read chunk 0
+                        r[u][t] = *reinterpret_cast<const Raw*>(p.x + row_off + (chunk < p.chunks ? (int64_t)chunk * VB : 0));
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < R; ++u) {
+                if (i0 + u < cnt) {
+#pragma unroll
+                    for (int t = 0; t < MT; ++t)
+                        if (t < tiles) C::add(acc[t], r[u][t]);
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            const int chunk = t * kWave + lane;
+            if (t < tiles && chunk < p.chunks) {
+#pragma unroll
+                for (int e = 0; e < VE; ++e) acc[t][e] *= inv;
+                *reinterpret_cast<Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc[t]);
+            }
+        }
+        return;
+    }
 
     const int sub = p.sub;
     const int sg = lane >> p.sub_shift;         // sub-group index within the wave
@@ -134,7 +181,7 @@ __device__ __forceinline__ void wave_mean_of_rows(const FwdParams& p, int id, in
 // ---------------------------------------------------------------------------------------
 // 1-hop: wave per seed
 // ---------------------------------------------------------------------------------------
-template <typename XT, int VB, bool REPLAY>
+template <typename XT, int VB, bool REPLAY, int MT>
 __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
@@ -145,12 +192,12 @@ __global__ __launch_bounds__(256) void fwd1_kernel(const FwdParams p) {
 
     int id = hop0_id<REPLAY>(p, b, lane);
     if (!REPLAY && p.out_ids1 && lane < p.k1) p.out_ids1[b * p.k1 + lane] = id;
-    wave_mean_of_rows<XT, VB>(p, id, ids, lane, p.out + b * p.row_bytes);
+    wave_mean_of_rows<XT, VB, MT>(p, id, ids, lane, p.out + b * p.row_bytes);
 }
 
 // Mean over the hop-1 slots that took part of the per-slot rows of a [B,k1,D] table (the last
 // step of a chained, deeper-hop call): lane j names row b*k1+j when slot_cnt[b,j] > 0.
-template <typename XT, int VB>
+template <typename XT, int VB, int MT>
 __global__ __launch_bounds__(256) void slot_mean_kernel(const FwdParams p) {
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
@@ -158,7 +205,7 @@ __global__ __launch_bounds__(256) void slot_mean_kernel(const FwdParams p) {
     const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
     if (b >= p.B) return;                       // wave-uniform; no block barrier below
     const int id = (lane < p.k1 && p.slot_cnt[b * p.k1 + lane] > 0) ? (int)(b * p.k1 + lane) : -1;
-    wave_mean_of_rows<XT, VB>(p, id, smem + wave * kWave, lane, p.out + b * p.row_bytes);
+    wave_mean_of_rows<XT, VB, MT>(p, id, smem + wave * kWave, lane, p.out + b * p.row_bytes);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -572,32 +619,44 @@ template <typename XT, int VB>
 static hipError_t launch_typed(const FwdArgs& a, const FwdParams& p, hipStream_t stream) {
     constexpr int VE = Chunk<XT, VB>::VE;
     const bool replay = a.indptr == nullptr;
+    // rows of 2 .. kMultiTiles tiles of 64 lanes take the row-major multi-tile gather
+    const int tiles = a.geom.tiles;
+    const int mt = (tiles <= 1 || tiles > kMultiTiles) ? 0 : (tiles <= 4 ? 4 : 8);
     if (a.slot_cnt) {                           // mean over the per-slot rows of a [B,k1,D] table
         const int wpb = 4;
-        const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
-        hipLaunchKernelGGL((slot_mean_kernel<XT, VB>), dim3(grid), dim3(wpb * kWave), sizeof(int) * kWave * wpb, stream, p);
+        const dim3 grid((unsigned)((a.B + wpb - 1) / wpb)), block(wpb * kWave);
+        const size_t lds = sizeof(int) * kWave * wpb;
+        if (mt == 0)      hipLaunchKernelGGL((slot_mean_kernel<XT, VB, 0>), grid, block, lds, stream, p);
+        else if (mt == 4) hipLaunchKernelGGL((slot_mean_kernel<XT, VB, 4>), grid, block, lds, stream, p);
+        else              hipLaunchKernelGGL((slot_mean_kernel<XT, VB, 8>), grid, block, lds, stream, p);
         return hipGetLastError();
     }
     if (a.hops == 1) {
         static const int wpb = [] { int v = env_int("FSA_FWD1_WAVES", 4); return v >= 1 && v <= 4 ? v : 4; }();
-        const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
+        const dim3 grid((unsigned)((a.B + wpb - 1) / wpb)), block(wpb * kWave);
         const size_t lds = sizeof(int) * kWave * wpb;
-        if (replay) hipLaunchKernelGGL((fwd1_kernel<XT, VB, true>), dim3(grid), dim3(wpb * kWave), lds, stream, p);
-        else        hipLaunchKernelGGL((fwd1_kernel<XT, VB, false>), dim3(grid), dim3(wpb * kWave), lds, stream, p);
+#define FSA_LAUNCH_FWD1(MT_)                                                                                   \
+        do {                                                                                                   \
+            if (replay) hipLaunchKernelGGL((fwd1_kernel<XT, VB, true, MT_>), grid, block, lds, stream, p);     \
+            else        hipLaunchKernelGGL((fwd1_kernel<XT, VB, false, MT_>), grid, block, lds, stream, p);    \
+        } while (0)
+        if (mt == 0) FSA_LAUNCH_FWD1(0);
+        else if (mt == 4) FSA_LAUNCH_FWD1(4);
+        else FSA_LAUNCH_FWD1(8);
+#undef FSA_LAUNCH_FWD1
     } else {
         const int nw = fwd2_waves(a.B, a.k1, a.geom);
         const int nq_max = (a.k1 + nw - 1) / nw;
         const size_t lds = sizeof(int) * ((size_t)nw * (4 * nq_max * a.k2 + 2 * nq_max) + nw)
                          + sizeof(float) * (size_t)nw * a.geom.sub * VE;
         const dim3 grid((unsigned)a.B), block(nw * kWave);
-        const int tiles = a.geom.tiles;
 #define FSA_LAUNCH_FWD2(MT_)                                                                                   \
         do {                                                                                                   \
             if (replay) hipLaunchKernelGGL((fwd2_kernel<XT, VB, true, MT_>), grid, block, lds, stream, p);     \
             else        hipLaunchKernelGGL((fwd2_kernel<XT, VB, false, MT_>), grid, block, lds, stream, p);    \
         } while (0)
-        if (tiles <= 1 || tiles > kMultiTiles) FSA_LAUNCH_FWD2(0);
-        else if (tiles <= 4) FSA_LAUNCH_FWD2(4);
+        if (mt == 0) FSA_LAUNCH_FWD2(0);
+        else if (mt == 4) FSA_LAUNCH_FWD2(4);
         else FSA_LAUNCH_FWD2(8);
 #undef FSA_LAUNCH_FWD2
     }
