@@ -142,3 +142,66 @@ def test_row_offsets_beyond_32_bits(fsa, orc):
     _forward_parity(fsa, orc, w, seeds, "wide offsets")
     w1 = synth.Workload("wide", w.graph, x, seeds.shape[0], (20,))
     _forward_parity(fsa, orc, w1, seeds, "wide offsets 1-hop")
+
+
+def test_products_shape_three_hop(fsa, orc):
+    """The product-graph shape with a third hop (fanouts [15,10,5], B=1024): IDs of all three
+    levels, per-slot counts, every mean and the gradient of the touched rows against the oracle."""
+    from paper_2511_13645_amd import synth
+    w, seeds = _build("products")
+    g, x = w.graph, w.x
+    N, D = x.shape
+    fan = [15, 10, 5]
+    r = fsa.fsa_sample_mean3_fwd(g.indptr, g.indices, x, seeds.cuda(), fan, w.sampler_seed)
+    torch.cuda.synchronize()
+    h_indptr, h_indices, hx = g.indptr.cpu().numpy(), g.indices.cpu().numpy(), x.cpu().numpy()
+    t0 = time.time()
+    ref = orc.sample_mean3_fwd(h_indptr, h_indices, hx, seeds.numpy(), fan, w.sampler_seed, want_h2=False)
+    print("[products 3-hop] oracle forward %.1fs, %d leaf rows" % (time.time() - t0, int((ref["ids3"] >= 0).sum())), flush=True)
+    for k in ("ids1", "ids2", "ids3", "cnt2"):
+        assert_ids_equal(r[k], ref[k], "products 3-hop " + k)
+    scale = orc.mean3_replay_fwd(np.abs(hx), ref["ids1"], ref["ids2"], ref["ids3"], want_h2=False)
+    worst = max(assert_close(to_f64(r[k]), ref[k], scale[k], 1e-5, "products 3-hop " + k) for k in ("out", "out_h1", "out_m1"))
+    print("[products 3-hop] ids bit-exact; worst relative error of the means %.2e" % worst, flush=True)
+    B, k1 = ref["ids1"].shape
+    gout = synth.upstream_grad((B, D), seed=3, device="cuda:0")
+    gh1 = synth.upstream_grad((B, k1, D), seed=4, device="cuda:0")
+    gx = torch.zeros((N, D), dtype=torch.float32, device="cuda:0")
+    fsa.fsa_mean3_bwd(gout, r["ids1"], r["ids2"], r["ids3"], grad_h1=gh1, grad_x=gx)
+    torch.cuda.synchronize()
+    want = orc.mean3_bwd(to_f64(gout), ref["ids1"], ref["ids2"], ref["ids3"], grad_h1=to_f64(gh1), num_nodes=N)
+    mag = orc.mean3_bwd(np.abs(to_f64(gout)), ref["ids1"], ref["ids2"], ref["ids3"], grad_h1=np.abs(to_f64(gh1)), num_nodes=N)
+    touched = np.unique(ref["ids3"][ref["ids3"] >= 0])
+    got = gx[torch.from_numpy(touched).cuda().long()].double().cpu().numpy()
+    worst = assert_close(got, want[touched], mag[touched], 1e-5, "products 3-hop grad_x (touched rows)")
+    total = float(gx.double().abs().sum().item())
+    assert abs(total - np.abs(got).sum()) <= 1e-6 * max(1.0, total)
+    print("[products 3-hop] grad_x over %d touched rows: worst relative error %.2e" % (touched.size, worst), flush=True)
+
+
+def test_social_shape_backward_into_bf16_table(fsa, orc):
+    """The dense social shape at full size with bf16 upstream gradients into a bf16 grad_x by
+    packed atomics: within (n+1) * (2^-8 * sum|contribution| + 2^-133) of the oracle, n = number
+    of additions into the row."""
+    from paper_2511_13645_amd import synth
+    w, seeds = _build("social")
+    g, x = w.graph, w.x
+    N, D = x.shape
+    fan = list(w.fanouts)
+    _, _, ids1, ids2 = fsa.fsa_sample_mean_fwd(g.indptr, g.indices, x, seeds.cuda(), fan, w.sampler_seed, emit_h1=False)
+    B, k1 = ids1.shape
+    gout = synth.upstream_grad((B, D), seed=3, device="cuda:0").to(torch.bfloat16)
+    gh1 = synth.upstream_grad((B, k1, D), seed=4, device="cuda:0").to(torch.bfloat16)
+    gx = torch.zeros((N, D), dtype=torch.bfloat16, device="cuda:0")
+    fsa.fsa_mean_bwd_lp(gout, ids1, ids2, gh1, grad_x=gx)
+    torch.cuda.synchronize()
+    h1, h2 = ids1.cpu().numpy(), ids2.cpu().numpy()
+    want = orc.mean_bwd(to_f64(gout), h1, h2, to_f64(gh1), num_nodes=N)
+    mag = orc.mean_bwd(np.abs(to_f64(gout)), h1, h2, np.abs(to_f64(gh1)), num_nodes=N)
+    n_add = np.bincount(h2[h2 >= 0], minlength=N).astype(np.float64)[:, None]
+    err = np.abs(to_f64(gx) - want)
+    bound = (n_add + 1.0) * (2.0 ** -8 * mag + 2.0 ** -133)
+    assert (err <= bound).all(), "worst excess %g" % float((err - bound).max())
+    assert (to_f64(gx)[n_add[:, 0] == 0] == 0).all()
+    print("[social bf16 backward] worst error / bound %.3f over %d touched rows" %
+          (float((err / np.maximum(bound, 1e-300)).max()), int((n_add > 0).sum())), flush=True)
