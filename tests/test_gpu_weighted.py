@@ -47,8 +47,8 @@ def _run(fsa, orc, indptr, indices, ew, x, seeds, fan, seed, what, check_bwd=Tru
     dev = "cuda:0"
     d_indptr, d_indices = torch.from_numpy(indptr).to(dev), torch.from_numpy(indices).to(dev)
     d_ew, d_x, d_seeds = torch.from_numpy(ew).to(dev), x.to(dev), torch.from_numpy(seeds).to(dev)
-    tol = TOL[x.dtype]
-    hx, is_bf16 = host_x(x)
+    tol = 1e-3 if x.dtype == torch.float16 else TOL[x.dtype]     # fp16: one rounding, half an ulp = 2^-11
+    hx, is_bf16 = (x.to(torch.float64).numpy(), False) if x.dtype == torch.float16 else host_x(x)
     r_out, r_h1, r_ids1, r_ids2, r_w1, r_w2 = orc.sample_wmean_fwd(indptr, indices, ew, hx, seeds, fan, seed, bf16=is_bf16)
     out, h1, ids1, ids2, w1, w2 = fsa.fsa_sample_wmean_fwd(d_indptr, d_indices, d_ew, d_x, d_seeds, fan, seed)
     torch.cuda.synchronize()
@@ -101,6 +101,16 @@ def test_weighted_bf16_wide_indptr(fsa, orc, D, fan):
     x = torch.from_numpy(np.random.default_rng(D).standard_normal((n, D)).astype(np.float32)).to(torch.bfloat16)
     seeds = np.concatenate([np.arange(24), np.random.default_rng(2).integers(0, n, 150)]).astype(np.int32)
     _run(fsa, orc, indptr, indices, ew, x, seeds, fan, 5, "weighted bf16 D=%d fan=%s" % (D, fan), check_bwd=False)
+
+
+@pytest.mark.parametrize("D", [2, 128, 330])
+@pytest.mark.parametrize("fan", [[15], [15, 10]])
+def test_weighted_fp16(fsa, orc, D, fan):
+    n = 2000
+    indptr, indices, ew = _graph(n, seed=70 + D)
+    x = torch.from_numpy(np.random.default_rng(D).standard_normal((n, D)).astype(np.float32)).to(torch.float16)
+    seeds = np.concatenate([np.arange(24), np.random.default_rng(2).integers(0, n, 150)]).astype(np.int32)
+    _run(fsa, orc, indptr, indices, ew, x, seeds, fan, 6, "weighted fp16 D=%d fan=%s" % (D, fan), check_bwd=False)
 
 
 def test_unit_weights_equal_the_unweighted_kernels(fsa):
