@@ -313,6 +313,18 @@ def main() -> int:
     ms_per_step = wall * 1e3 / steps
     kern_ms = ev_ms / steps
 
+    # per-launch durations (median, p10, p90) from an event pair around each launch of a second,
+    # untimed pass over the same batches (the paper's protocol reports the median of 200)
+    n_pl = min(steps, 200)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_pl)]
+    for i in range(n_pl):
+        evs[i][0].record()
+        step(warmup + i)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    per_launch = sorted(a.elapsed_time(b_) * 1e3 for a, b_ in evs)
+    pct = {"median": per_launch[n_pl // 2], "p10": per_launch[n_pl // 10], "p90": per_launch[(9 * n_pl) // 10]}
+
     # what the timed launches actually aggregated
     leaf_rows = 0
     hop1_rows = 0
@@ -488,6 +500,27 @@ def main() -> int:
         cpu = {"value": done_rows / spent, "unit": "rows/s", "cores": 1, "kind": "oracle",
                "sample": "%d of the timed batches (B=%d each), %.1f s of single-thread oracle "
                          "(sampling + fp64 means, same graph and table on the host)" % (done_batches, sample_b, spent)}
+        # the same unchanged oracle on every host core: this harness cuts a batch into one
+        # contiguous slice of seeds per thread (ctypes releases the interpreter lock in the call)
+        from concurrent.futures import ThreadPoolExecutor
+        n_thr = max(1, min(int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or (os.cpu_count() or 1), os.cpu_count() or 1))
+        if n_thr > 1 and B >= n_thr:
+            bounds = [B * t // n_thr for t in range(n_thr + 1)]
+
+            def run_slice(args_):
+                sb, lo, hi = args_
+                r = oracle.sample_mean_fwd(h_indptr, h_indices, h_x, sb[lo:hi], fan, w.sampler_seed, bf16=is_bf16)
+                return int((r[3] >= 0).sum()) if hops == 2 else int((r[2] >= 0).sum())
+            rows_mt, batches_mt, spent_mt = 0, 0, 0.0
+            with ThreadPoolExecutor(max_workers=n_thr) as pool:
+                while spent_mt < max(2.0, args.cpu_seconds / 3):
+                    sb = h_seeds[warmup + batches_mt % steps]
+                    c0 = time.perf_counter()
+                    rows_mt += sum(pool.map(run_slice, [(sb, bounds[t], bounds[t + 1]) for t in range(n_thr)]))
+                    spent_mt += time.perf_counter() - c0
+                    batches_mt += 1
+            cpu["all_cores"] = {"value": rows_mt / spent_mt, "unit": "rows/s", "cores": n_thr,
+                                "sample": "%d batches in %.1f s, one slice of seeds per thread" % (batches_mt, spent_mt)}
 
     line = {
         "metric": "sampled neighbor rows aggregated/sec + achieved HBM GB/s, fanout %s D=%d" % ("/".join(map(str, fan)), D),
@@ -502,7 +535,8 @@ def main() -> int:
         "hbm_gbps": achieved,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "fwd2_kernel" if hops == 2 else "fwd1_kernel", "launch_us": kern_ms * 1e3},
+                     "kernel": "fwd2_kernel" if hops == 2 else "fwd1_kernel", "launch_us": kern_ms * 1e3,
+                     "launch_us_event_pairs": pct},
         "cpu_baseline": cpu,
         "saturated": saturated,
         "other_paths": other_paths,
