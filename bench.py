@@ -428,6 +428,18 @@ def main() -> int:
                                 "atomic_payload_gbps": payload / (b_ms * 1e-3) / 1e9,
                                 "hbm_gbps": b_alg / (b_ms * 1e-3) / 1e9,
                                 "frac": b_alg / (b_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            if "grad_x_zero_fill" not in other_paths or gx_dt == torch.float32:
+                # the caller's zero-fill of the gradient table, never part of the backward's time
+                grad_x.zero_()
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(3):
+                    grad_x.zero_()
+                e1.record()
+                torch.cuda.synchronize()
+                other_paths["grad_x_zero_fill"] = {"launch_us": e0.elapsed_time(e1) / 3 * 1e3,
+                                                   "bytes": grad_x.numel() * grad_x.element_size(),
+                                                   "dtype": str(gx_dt).split(".")[1]}
             del g_out, g_h1, grad_x
         log("[bench] other paths: %s" % json.dumps(other_paths))
 
