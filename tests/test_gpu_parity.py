@@ -268,3 +268,33 @@ def test_very_wide_rows_and_large_batch(fsa, orc):
     seeds = rng.integers(0, n, 70_001).astype(np.int32)
     run_case(fsa, orc, indptr, indices, x, seeds, [4, 3], 2, what="B=70001 2-hop")
     run_case(fsa, orc, indptr, indices, x, seeds, [5], 2, what="B=70001 1-hop")
+
+
+@pytest.mark.parametrize("B,fan,D,bf16", [(4096, [15, 10], 64, False), (2048, [15, 10], 128, True),
+                                          (8192, [9, 4], 40, False), (5000, [64, 3], 32, False), (4096, [8, 64], 602, False)])
+def test_mid_size_batches_with_roots_of_every_weight(fsa, orc, B, fan, D, bf16):
+    """Batches of 2048..8192 roots (one or two waves per root, every root resident at once): roots
+    of every weight (no slots, a few, all of them) next to each other -- forward, emission off,
+    replay (also with holes that change a root's weight) and backward."""
+    n = 6000
+    indptr, indices = ragged_graph(n, seed=B % 97, max_deg=30, hub_deg=3000)
+    rng = np.random.default_rng(B)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    if bf16:
+        x = x.to(torch.bfloat16)
+    seeds = np.concatenate([np.arange(8), rng.integers(0, n, B - 8)]).astype(np.int32)
+    out, h1, ids1, ids2 = run_case(fsa, orc, indptr, indices, x, seeds, fan, 1234, check_bwd=not bf16,
+                                   what="mid-size B=%d fan=%s" % (B, fan))
+    # replay with holes: roots become lighter or empty
+    h_ids1, h_ids2 = ids1.cpu().numpy().copy(), ids2.cpu().numpy().copy()
+    h_ids1[rng.random(h_ids1.shape) < 0.5] = -1
+    h_ids2[rng.random(h_ids2.shape) < 0.3] = -1
+    hx, is_bf16 = host_x(x)
+    r_out, r_h1 = orc.mean_replay_fwd(hx, h_ids1, h_ids2, bf16=is_bf16)
+    d_x = x.to("cuda:0")
+    d1, d2 = torch.from_numpy(h_ids1).to("cuda:0"), torch.from_numpy(h_ids2).to("cuda:0")
+    g_out, g_h1 = fsa.fsa_mean_replay_fwd(d_x, d1, d2)
+    torch.cuda.synchronize()
+    a_out, a_h1 = forward_scales(d_x, d1, torch.where(d1[..., None] >= 0, d2, torch.full_like(d2, -1)))
+    assert_close(to_f64(g_out), r_out, a_out, TOL[x.dtype], "mid-size replay holes out")
+    assert_close(to_f64(g_h1), r_h1, a_h1, TOL[x.dtype], "mid-size replay holes h1")
