@@ -137,7 +137,11 @@ __global__ __launch_bounds__(256) void wfwd1_kernel(const WFwdParams p) {
 // ---------------------------------------------------------------------------------------
 constexpr int kWPassGroup = 4;
 
-template <typename XT, int VB, bool REPLAY>
+// MT > 0: rows of 2 .. MT tiles of 64 lanes, all tiles of a row loaded back to back (the same
+// wide-row gather as the unweighted kernel); MT = 0: one list walk per tile.
+constexpr int kWMultiTiles = 8;
+
+template <typename XT, int VB, bool REPLAY, int MT>
 __global__ __launch_bounds__(512) void wfwd2_kernel(const WFwdParams p) {
     using C = Chunk<XT, VB>;
     using Raw = typename C::Raw;
@@ -294,6 +298,101 @@ __global__ __launch_bounds__(512) void wfwd2_kernel(const WFwdParams p) {
     }
     __builtin_amdgcn_wave_barrier();
 
+    if constexpr (MT > 0) {
+        // sub == 64: the wave walks its whole list, one row (all its tiles) at a time
+        const int tiles = (p.chunks + kWave - 1) >> 6;
+        float acc[MT][VE], root[MT][VE];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) { acc[t][e] = 0.0f; root[t][e] = 0.0f; }
+        }
+        float wacc = 0.0f, rootw = 0.0f;
+        if (p.out_h1) {                                              // empty slots get zero rows
+            for (int i = 0; i < n_empty; ++i) {
+                char* dst = p.out_h1 + (b * k1 + wave + empty_q[i] * nw) * p.row_bytes;
+                for (int chunk = lane; chunk < p.chunks; chunk += kWave)
+                    *reinterpret_cast<Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc[0]);
+            }
+        }
+        for (int i = 0; i < total; ++i) {
+            const int2 ent = flat[i];
+            const float wr = flat_w[i];
+            const uint64_t row_off = ((uint64_t)((uint32_t)ent.y & 0x7fffffffu) << 32) | (uint32_t)ent.x;
+            Raw r[MT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                if (t < tiles) {                                     // wave-uniform
+                    const int chunk = t * kWave + lane;              // lanes past the row width re-read chunk 0
+                    r[t] = *reinterpret_cast<const Raw*>(p.x + row_off + (chunk < p.chunks ? (int64_t)chunk * VB : 0));
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+                if (t < tiles) C::fma(acc[t], r[t], wr);
+            wacc += wr;
+            if (ent.y < 0) {                                         // last row of its slot
+                const int meta = flat_meta[i];
+                const float a = slot_a[meta >> 8];
+                const bool part = wacc > 0.0f;
+                const float inv = part ? __builtin_amdgcn_rcpf(wacc) : 0.0f;
+                char* dst = p.out_h1 ? p.out_h1 + (b * k1 + (meta & 0xff)) * p.row_bytes : nullptr;
+#pragma unroll
+                for (int t = 0; t < MT; ++t) {
+                    if (t < tiles) {
+                        const int chunk = t * kWave + lane;
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) {
+                            acc[t][e] = part ? acc[t][e] * inv : 0.0f;
+                            root[t][e] = fmaf(part ? a : 0.0f, acc[t][e], root[t][e]);
+                        }
+                        if (dst && chunk < p.chunks)
+                            *reinterpret_cast<Raw*>(dst + (int64_t)chunk * VB) = C::pack(acc[t]);
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) acc[t][e] = 0.0f;
+                    }
+                }
+                rootw += part ? a : 0.0f;
+                wacc = 0.0f;
+            }
+        }
+        if (nw > 1 && lane == 0) red_w[wave] = rootw;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            if (t < tiles) {                                         // workgroup-uniform
+                const int chunk = t * kWave + lane;
+                const bool live = chunk < p.chunks;
+                if (nw == 1) {
+                    const float inv1 = rootw > 0.0f ? __builtin_amdgcn_rcpf(rootw) : 0.0f;
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) root[t][e] = rootw > 0.0f ? root[t][e] * inv1 : 0.0f;
+                    if (live) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(root[t]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) red[(wave * kWave + lane) * VE + e] = root[t][e];
+                    __syncthreads();
+                    if (wave == 0) {
+                        float tot[VE];
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) tot[e] = 0.0f;
+                        float totw = 0.0f;
+                        for (int w = 0; w < nw; ++w) {
+#pragma unroll
+                            for (int e = 0; e < VE; ++e) tot[e] += red[(w * kWave + lane) * VE + e];
+                            totw += red_w[w];
+                        }
+                        const float inv1 = totw > 0.0f ? __builtin_amdgcn_rcpf(totw) : 0.0f;
+#pragma unroll
+                        for (int e = 0; e < VE; ++e) tot[e] = totw > 0.0f ? tot[e] * inv1 : 0.0f;
+                        if (live) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(tot);
+                    }
+                    __syncthreads();                                 // red is reused by the next tile
+                }
+            }
+        }
+        return;
+    }
+
     for (int c0 = 0; c0 < p.chunks; c0 += sub) {
         const int chunk = c0 + sl;
         const bool live = chunk < p.chunks;
@@ -403,8 +502,17 @@ static hipError_t launch_typed_w(const FwdArgs& a, const WFwdParams& p, hipStrea
         const int nq_max = (a.k1 + nw - 1) / nw;
         const size_t per_wave = ((size_t)6 * nq_max * a.k2 + 3 * nq_max + 1) & ~(size_t)1;
         const size_t lds = sizeof(int) * (nw * per_wave + nw) + sizeof(float) * (size_t)nw * a.geom.sub * VE;
-        if (replay) hipLaunchKernelGGL((wfwd2_kernel<XT, VB, true>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
-        else        hipLaunchKernelGGL((wfwd2_kernel<XT, VB, false>), dim3((unsigned)a.B), dim3(nw * kWave), lds, stream, p);
+        const dim3 grid((unsigned)a.B), block(nw * kWave);
+        const int tiles = a.geom.tiles;
+#define FSA_LAUNCH_WFWD2(MT_)                                                                                  \
+        do {                                                                                                   \
+            if (replay) hipLaunchKernelGGL((wfwd2_kernel<XT, VB, true, MT_>), grid, block, lds, stream, p);    \
+            else        hipLaunchKernelGGL((wfwd2_kernel<XT, VB, false, MT_>), grid, block, lds, stream, p);   \
+        } while (0)
+        if (tiles <= 1 || tiles > kWMultiTiles) FSA_LAUNCH_WFWD2(0);
+        else if (tiles <= 4) FSA_LAUNCH_WFWD2(4);
+        else FSA_LAUNCH_WFWD2(8);
+#undef FSA_LAUNCH_WFWD2
     }
     return hipGetLastError();
 }
