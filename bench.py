@@ -222,6 +222,9 @@ def main() -> int:
                     help="convert the workload's feature table to this type first (fp32 variant of the headline)")
     ap.add_argument("--three-hop", type=int, default=0, metavar="K3",
                     help="time the three-hop forward (workload fanouts + K3) instead of the workload's own path")
+    ap.add_argument("--ceilings", type=int, default=0, metavar="GB",
+                    help="first measure what this GPU sustains on plain access patterns over a table of GB GiB "
+                         "(streaming read, copy, random row gather, row atomics, row stores); adds `ceilings`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
     args = ap.parse_args()
@@ -247,6 +250,24 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    ceilings = None
+    if args.ceilings:
+        from paper_2511_13645_amd import build as hip_build
+        if not os.path.exists(hip_build.CEILINGS_LIB):
+            raise RuntimeError("libfsa_ceilings.so missing: build it with __graft_entry__.build()")
+        C = ctypes.CDLL(hip_build.CEILINGS_LIB)
+        C.fsa_ceilings_measure.argtypes = [ctypes.c_int, ctypes.c_void_p]
+        C.fsa_ceilings_measure.restype = ctypes.c_int
+        vals = (ctypes.c_double * 7)()
+        torch.cuda.synchronize()
+        rc = C.fsa_ceilings_measure(args.ceilings, ctypes.cast(vals, ctypes.c_void_p))
+        if rc != 0:
+            raise RuntimeError("fsa_ceilings_measure -> %d" % rc)
+        names = ("streaming_read", "copy_read_plus_write", "gather_256B_rows", "gather_512B_rows",
+                 "atomic_add_f32_512B_rows", "atomic_pk_add_bf16_256B_rows", "store_512B_rows")
+        ceilings = {"unit": "GB/s", "table_gib": args.ceilings, **{n: vals[i] for i, n in enumerate(names)}}
+        log("[bench] ceilings: %s" % json.dumps(ceilings))
 
     t0 = time.time()
     w = load_or_make_workload(args.workload, args.scale, args.cache, dev)
@@ -553,6 +574,7 @@ def main() -> int:
         "saturated": saturated,
         "other_paths": other_paths,
         "batch_sweep": batch_sweep,
+        "ceilings": ceilings,
     }
     print(json.dumps(line), flush=True)
     return 0

@@ -162,6 +162,20 @@ def test_layerwise_and_three_hop_entry_points_reject_bad_arguments(fsa):
     assert b3(k2=0) == -2 and b3(D=0) == -2 and b3(w=FAKE + 2) == -4 and b3(B=0) == 0 and b3(B=0, w=None) == 0
 
 
+def test_ceilings_library_builds_and_exports_its_entry_point():
+    """The measurement aid of bench.py --ceilings: its own library, one entry point, bad arguments refused
+    before anything touches a GPU."""
+    from paper_2511_13645_amd import build
+    if not os.path.exists(build.CEILINGS_LIB):
+        build.build_ceilings()
+    C = ctypes.CDLL(build.CEILINGS_LIB)
+    C.fsa_ceilings_measure.argtypes = [ctypes.c_int, ctypes.c_void_p]
+    C.fsa_ceilings_measure.restype = ctypes.c_int
+    out = (ctypes.c_double * 7)()
+    assert C.fsa_ceilings_measure(2, ctypes.cast(out, ctypes.c_void_p)) == -1     # table too small
+    assert C.fsa_ceilings_measure(28, None) == -1
+
+
 def test_binding_fails_loudly_without_library(fsa, monkeypatch):
     monkeypatch.setattr(fsa, "_lib", None)
     monkeypatch.setattr(fsa, "LIB_PATH", "/nonexistent/libfsa_hip.so")
