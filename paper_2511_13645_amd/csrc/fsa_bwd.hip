@@ -114,8 +114,8 @@ __device__ __forceinline__ void merge_equal_ids(int id, int k, int li, int seg_b
 }
 
 // ---------------------------------------------------------------------------------------
-// 1-hop backward.  A workgroup of 4 waves takes 4*spw consecutive seeds (wave w the seeds
-// w, w+4, ...).  Rows that many seeds of the workgroup share -- the hub rows of a skewed
+// 1-hop backward.  A workgroup of nw (16) waves takes nw*spw consecutive seeds (wave w the
+// seeds w, w+nw, ...).  Rows that many seeds of the workgroup share -- the hub rows of a skewed
 // graph, which would otherwise serialise thousands of atomics on one L2 channel -- are first
 // summed in LDS and reach grad_x with ONE atomic row-add per workgroup:
 //   pass 1  every sampled ID bumps an LDS counter at hash(id);
@@ -138,7 +138,7 @@ __device__ __forceinline__ int hot_hash(int id) {
 }
 
 template <typename GT, typename XG>
-__global__ __launch_bounds__(256) void bwd1_kernel(const BwdParams p, int spw, int hot_rows) {
+__global__ __launch_bounds__(1024) void bwd1_kernel(const BwdParams p, int spw, int hot_rows) {
     constexpr int EPL = Epl<GT, XG>::value;
     extern __shared__ int smem[];
     const int lane = threadIdx.x & 63;
@@ -412,19 +412,25 @@ static int env_int(const char* name, int fallback) {
 template <typename GT, typename XG>
 static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hipStream_t stream) {
     if (!a.ids2) {
-        // seeds per wave: more seeds per workgroup merge more hub traffic, but small batches
-        // must still spread over the chip
+        // Workgroups of 16 waves: the rows the seeds of a workgroup share are merged in LDS, so the
+        // more seeds a workgroup sees the fewer atomic row-adds reach a hub row, and 16 waves work
+        // through them side by side.  Seeds per wave grow with the batch so that the launch keeps
+        // a few hundred workgroups (measured on the KG shape, B = 1024 .. 262144: 14.7 us at
+        // B=4096 against 20.4 us with 4-wave workgroups, 84 against 136 us at B=65536).
         static const int forced_spw = env_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
-        const int nw = 4;
-        int spw = 2;
-        while (spw < 16 && a.B / (spw * 2) >= 4096) spw *= 2;   // 2 up to B=16k, 16 from B=64k
+        static const int forced_nw = env_int("FSA_BWD1_WAVES", 0);
+        const int nw = (forced_nw >= 1 && forced_nw <= 16) ? forced_nw : 16;
+        int spw = 1;
+        while (spw < 16 && a.B / ((int64_t)nw * spw * 2) >= 256) spw *= 2;
         if (forced_spw >= 1 && forced_spw <= 64) spw = forced_spw;
-        int hot_rows = (int)(8192 / a.D);                    // at most 32 KB of LDS rows
+        // LDS: the fixed part (hash tables, per-wave strips) plus as many fp32 rows as fit in 64 KB
+        const size_t lds_fixed = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave);
+        int hot_rows = (int)((65536 - lds_fixed) / (sizeof(float) * (size_t)a.D));
         if (hot_rows > kHotRowsMax) hot_rows = kHotRowsMax;
         static const int no_hot = env_int("FSA_BWD1_NO_HOT", 0);
         if (no_hot) hot_rows = 0;
         const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
-        const size_t lds = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave) + sizeof(float) * (size_t)hot_rows * a.D;
+        const size_t lds = lds_fixed + sizeof(float) * (size_t)hot_rows * a.D;
         hipLaunchKernelGGL((bwd1_kernel<GT, XG>), dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
     } else {
         static const int forced = env_int("FSA_BWD2_WAVES", 0);
