@@ -220,6 +220,8 @@ def main() -> int:
                     "with and without ID / per-slot emission, on the same graph")
     ap.add_argument("--feature-dtype", default="", choices=["", "f32", "bf16"],
                     help="convert the workload's feature table to this type first (fp32 variant of the headline)")
+    ap.add_argument("--weighted", action="store_true",
+                    help="also time the weighted-mean forward, replay and (fp32 tables) backward on the same batches")
     ap.add_argument("--three-hop", type=int, default=0, metavar="K3",
                     help="time the three-hop forward (workload fanouts + K3) instead of the workload's own path")
     ap.add_argument("--ceilings", type=int, default=0, metavar="GB",
@@ -464,6 +466,60 @@ def main() -> int:
             del g_out, g_h1, grad_x
         log("[bench] other paths: %s" % json.dumps(other_paths))
 
+    weighted = None
+    if args.weighted and emit:
+        # the weighted mean on the same batches: hashed uniform weights in [0,1) per edge
+        weighted = {}
+        n_p = min(steps, 50)
+        ew = synth.edge_weights(g.num_edges, seed=11, device=dev)
+        x_code_w = {torch.float32: binding.FSA_F32, torch.bfloat16: binding.FSA_BF16, torch.float16: binding.FSA_F16}[x.dtype]
+        w1 = torch.empty((n_p, B, k1), dtype=torch.float32, device=dev)
+        w2 = torch.empty((n_p, B, k1, k2), dtype=torch.float32, device=dev) if hops == 2 else None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+        def timed_w(fn):
+            for i in range(2):
+                fn(i)
+            torch.cuda.synchronize()
+            e0.record()
+            for i in range(n_p):
+                fn(i)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n_p * 1e3
+
+        def w_fwd(i):
+            rc = L.fsa_sample_wmean_fwd(fixed_head[0], fixed_head[1], fixed_head[2], ew.data_ptr(), N, x.data_ptr(), x_code_w, D,
+                                        seed_ptrs[warmup + i], B, ctypes.cast(fan_host, ctypes.c_void_p), hops, w.sampler_seed,
+                                        out.data_ptr(), None if out_h1 is None else out_h1.data_ptr(),
+                                        id1_ptrs[warmup + i], id2_ptrs[warmup + i], w1[i].data_ptr(),
+                                        None if w2 is None else w2[i].data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError("fsa_sample_wmean_fwd -> %d" % rc)
+
+        def w_replay(i):
+            rc = L.fsa_wmean_replay_fwd(x.data_ptr(), x_code_w, D, N, id1_ptrs[warmup + i], id2_ptrs[warmup + i], w1[i].data_ptr(),
+                                        None if w2 is None else w2[i].data_ptr(), B, k1, k2, out.data_ptr(),
+                                        None if out_h1 is None else out_h1.data_ptr(), stream)
+            if rc != 0:
+                raise RuntimeError("fsa_wmean_replay_fwd -> %d" % rc)
+        weighted["forward_us"] = timed_w(w_fwd)
+        weighted["replay_forward_us"] = timed_w(w_replay)
+        if x.dtype == torch.float32:
+            g_out = synth.upstream_grad((B, D), seed=3, device=dev)
+            grad_x = torch.zeros((N, D), dtype=torch.float32, device=dev)
+
+            def w_bwd(i):
+                rc = L.fsa_wmean_bwd(g_out.data_ptr(), None, id1_ptrs[warmup + i], id2_ptrs[warmup + i], w1[i].data_ptr(),
+                                     None if w2 is None else w2[i].data_ptr(), B, k1, k2, D, grad_x.data_ptr(), N, stream)
+                if rc != 0:
+                    raise RuntimeError("fsa_wmean_bwd -> %d" % rc)
+            weighted["backward_us"] = timed_w(w_bwd)
+            del g_out, grad_x
+        weighted["unweighted_forward_us"] = kern_ms * 1e3
+        del ew, w1, w2
+        log("[bench] weighted mean: %s" % json.dumps(weighted))
+
     def forward_at_batch(Bs, emit_s, n_launch=20):
         """Time `n_launch` back-to-back forward launches at batch size Bs on the same graph."""
         if Bs > N:                               # seeds are drawn without replacement
@@ -575,6 +631,7 @@ def main() -> int:
         "other_paths": other_paths,
         "batch_sweep": batch_sweep,
         "ceilings": ceilings,
+        "weighted": weighted,
     }
     print(json.dumps(line), flush=True)
     return 0

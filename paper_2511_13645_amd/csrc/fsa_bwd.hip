@@ -19,6 +19,7 @@ namespace fsa {
 struct BwdParams {
     const void* grad_out; const void* grad_h1; const int32_t* ids1; const int32_t* ids2;
     void* grad_x; int64_t B; int64_t D; int k1, k2;
+    const float* w1;                     // 1-hop weighted mean: [B,k1] weights of the sampled edges, else unused
     const int32_t* root_valid;           // 2-hop, nullable: [B], a negative entry switches root b off
 };
 
@@ -137,7 +138,7 @@ __device__ __forceinline__ int hot_hash(int id) {
     return (int)(((uint32_t)id * 2654435761u) >> 21);              // 11 bits -> kHotBuckets
 }
 
-template <typename GT, typename XG>
+template <typename GT, typename XG, bool WEIGHTED>
 __global__ __launch_bounds__(1024) void bwd1_kernel(const BwdParams p, int spw, int hot_rows) {
     constexpr int EPL = Epl<GT, XG>::value;
     extern __shared__ int smem[];
@@ -214,16 +215,33 @@ __global__ __launch_bounds__(1024) void bwd1_kernel(const BwdParams p, int spw, 
         const int64_t b = b0 + wave + (int64_t)s * nw;
         if (b >= p.B) break;                                         // wave-uniform
         const int id = lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
-        const int cnt = __popcll(__ballot(id >= 0));
-        int mult; bool first;
-        merge_equal_ids(id, p.k1, lane, 0, mult, first);
-        const bool keep = id >= 0 && first;
+        // share of the seed's gradient that this lane's row receives: multiplicity / count, or,
+        // for the weighted mean, the summed weight of its occurrences / the seed's weight sum
+        // (a seed whose weights sum to zero contributes nothing)
+        float share;
+        bool first;
+        bool live_seed = true;
+        if constexpr (WEIGHTED) {
+            const float w = id >= 0 ? p.w1[b * p.k1 + lane] : 0.0f;
+            float total = w;
+            for (int off = 1; off < kWave; off <<= 1) total += __shfl_xor(total, off);
+            float wsum;
+            merge_equal_ids_w(id, w, p.k1, lane, 0, wsum, first);
+            live_seed = total > 0.0f;
+            share = live_seed ? wsum / total : 0.0f;
+        } else {
+            const int cnt = __popcll(__ballot(id >= 0));
+            int mult;
+            merge_equal_ids(id, p.k1, lane, 0, mult, first);
+            share = (float)mult / (float)cnt;
+        }
+        const bool keep = id >= 0 && first && live_seed;
         const uint64_t kept = __ballot(keep);
         const int n = __popcll(kept);
         if (keep) {
             const int slot = __popcll(kept & lanemask_lt(lane));
             rows[slot] = id;
-            weight[slot] = (float)mult / (float)cnt;
+            weight[slot] = share;
             int hr = -1;
             if (any_hot) { const int h = hot_hash(id); if (tag[h] == id) hr = row_of[h]; }
             hot_of[slot] = hr;
@@ -409,29 +427,35 @@ static int env_int(const char* name, int fallback) {
     return v ? std::atoi(v) : fallback;
 }
 
+template <typename GT, typename XG, bool WEIGHTED>
+static hipError_t launch_bwd1(const BwdArgs& a, const BwdParams& p, hipStream_t stream) {
+    // Workgroups of 16 waves: the rows the seeds of a workgroup share are merged in LDS, so the
+    // more seeds a workgroup sees the fewer atomic row-adds reach a hub row, and 16 waves work
+    // through them side by side.  Seeds per wave grow with the batch so that the launch keeps
+    // a few hundred workgroups (measured on the KG shape, B = 1024 .. 262144: 14.7 us at
+    // B=4096 against 20.4 us with 4-wave workgroups, 84 against 136 us at B=65536).
+    static const int forced_spw = env_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
+    static const int forced_nw = env_int("FSA_BWD1_WAVES", 0);
+    const int nw = (forced_nw >= 1 && forced_nw <= 16) ? forced_nw : 16;
+    int spw = 1;
+    while (spw < 16 && a.B / ((int64_t)nw * spw * 2) >= 256) spw *= 2;
+    if (forced_spw >= 1 && forced_spw <= 64) spw = forced_spw;
+    // LDS: the fixed part (hash tables, per-wave strips) plus as many fp32 rows as fit in 64 KB
+    const size_t lds_fixed = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave);
+    int hot_rows = (int)((65536 - lds_fixed) / (sizeof(float) * (size_t)a.D));
+    if (hot_rows > kHotRowsMax) hot_rows = kHotRowsMax;
+    static const int no_hot = env_int("FSA_BWD1_NO_HOT", 0);
+    if (no_hot) hot_rows = 0;
+    const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
+    const size_t lds = lds_fixed + sizeof(float) * (size_t)hot_rows * a.D;
+    hipLaunchKernelGGL((bwd1_kernel<GT, XG, WEIGHTED>), dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
+    return hipGetLastError();
+}
+
 template <typename GT, typename XG>
 static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hipStream_t stream) {
     if (!a.ids2) {
-        // Workgroups of 16 waves: the rows the seeds of a workgroup share are merged in LDS, so the
-        // more seeds a workgroup sees the fewer atomic row-adds reach a hub row, and 16 waves work
-        // through them side by side.  Seeds per wave grow with the batch so that the launch keeps
-        // a few hundred workgroups (measured on the KG shape, B = 1024 .. 262144: 14.7 us at
-        // B=4096 against 20.4 us with 4-wave workgroups, 84 against 136 us at B=65536).
-        static const int forced_spw = env_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
-        static const int forced_nw = env_int("FSA_BWD1_WAVES", 0);
-        const int nw = (forced_nw >= 1 && forced_nw <= 16) ? forced_nw : 16;
-        int spw = 1;
-        while (spw < 16 && a.B / ((int64_t)nw * spw * 2) >= 256) spw *= 2;
-        if (forced_spw >= 1 && forced_spw <= 64) spw = forced_spw;
-        // LDS: the fixed part (hash tables, per-wave strips) plus as many fp32 rows as fit in 64 KB
-        const size_t lds_fixed = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave);
-        int hot_rows = (int)((65536 - lds_fixed) / (sizeof(float) * (size_t)a.D));
-        if (hot_rows > kHotRowsMax) hot_rows = kHotRowsMax;
-        static const int no_hot = env_int("FSA_BWD1_NO_HOT", 0);
-        if (no_hot) hot_rows = 0;
-        const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
-        const size_t lds = lds_fixed + sizeof(float) * (size_t)hot_rows * a.D;
-        hipLaunchKernelGGL((bwd1_kernel<GT, XG>), dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
+        return launch_bwd1<GT, XG, false>(a, p, stream);
     } else {
         static const int forced = env_int("FSA_BWD2_WAVES", 0);
         int nw = (forced >= 1 && forced <= 8) ? forced : (a.k1 < 8 ? a.k1 : 8);
@@ -445,7 +469,7 @@ static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hi
 hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
     BwdParams p;
     p.grad_out = a.grad_out; p.grad_h1 = a.grad_h1; p.ids1 = a.ids1; p.ids2 = a.ids2;
-    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2; p.root_valid = a.root_valid;
+    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2; p.root_valid = a.root_valid; p.w1 = nullptr;
     // kinds: 0 fp32, 1 bfloat16, 2 fp16.  A 16-bit grad_x takes gradients of its own type or fp32.
     switch (a.grad_kind * 3 + a.grad_x_kind) {
         case 0 * 3 + 0: return launch_backward_typed<g_f32, g_f32>(a, p, stream);
@@ -457,6 +481,14 @@ hipError_t launch_backward(const BwdArgs& a, hipStream_t stream) {
         case 2 * 3 + 2: return launch_backward_typed<g_f16, g_f16>(a, p, stream);
         default: return hipErrorInvalidValue;
     }
+}
+
+// 1-hop weighted-mean backward (fp32): the 1-hop kernel with weight shares.
+hipError_t launch_backward1_weighted(const BwdArgs& a, const float* w1, hipStream_t stream) {
+    BwdParams p;
+    p.grad_out = a.grad_out; p.grad_h1 = nullptr; p.ids1 = a.ids1; p.ids2 = nullptr;
+    p.grad_x = a.grad_x; p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = 0; p.root_valid = nullptr; p.w1 = w1;
+    return launch_bwd1<g_f32, g_f32, true>(a, p, stream);
 }
 
 }  // namespace fsa

@@ -281,4 +281,22 @@ __device__ __forceinline__ void sum_row_chunks(const char* __restrict__ x, int64
     }
 }
 
+// Sum of the weights of the lanes of a segment that carry this lane's ID, and whether this
+// lane is the first of them.
+__device__ __forceinline__ void merge_equal_ids_w(int id, float w, int k, int li, int seg_base, float& wsum,
+                                                  bool& first) {
+    wsum = 0.0f;
+    first = true;
+    for (int m0 = 0; m0 < k; m0 += 4) {
+        int other[4];
+        float ow[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { other[j] = __shfl(id, seg_base + m0 + j); ow[j] = __shfl(w, seg_base + m0 + j); }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (m0 + j < k && other[j] == id) { wsum += ow[j]; if (m0 + j < li) first = false; }
+        }
+    }
+}
+
 }  // namespace fsa

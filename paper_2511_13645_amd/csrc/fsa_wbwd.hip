@@ -1,7 +1,8 @@
-// Weighted-mean backward kernels: the adjoint, with respect to the feature table, of the
+// Weighted-mean backward, 2-hop: the adjoint, with respect to the feature table, of the
 // weighted replay forward (weights are data).  Same ownership and the same atomic row-adds as
 // the unweighted backward; the share of a sampled row is its weight over the slot's weight
 // sum instead of 1/count, and equal IDs inside a slot are merged by adding their weights.
+// The 1-hop case runs in the unweighted 1-hop kernel (fsa_bwd.hip) with weight shares.
 #include "fsa_device.hip.h"
 #include "fsa_internal.h"
 
@@ -13,58 +14,6 @@ struct WBwdParams {
 };
 
 __device__ __forceinline__ void w_atomic_add(float* addr, float v) { unsafeAtomicAdd(addr, v); }
-
-// Sum of the weights of the lanes of a segment that carry this lane's ID, and whether this
-// lane is the first of them.
-__device__ __forceinline__ void merge_equal_ids_w(int id, float w, int k, int li, int seg_base, float& wsum,
-                                                  bool& first) {
-    wsum = 0.0f;
-    first = true;
-    for (int m0 = 0; m0 < k; m0 += 4) {
-        int other[4];
-        float ow[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { other[j] = __shfl(id, seg_base + m0 + j); ow[j] = __shfl(w, seg_base + m0 + j); }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            if (m0 + j < k && other[j] == id) { wsum += ow[j]; if (m0 + j < li) first = false; }
-        }
-    }
-}
-
-__global__ __launch_bounds__(256) void wbwd1_kernel(const WBwdParams p) {
-    extern __shared__ int smem[];
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int64_t b = (int64_t)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (b >= p.B) return;                               // wave-uniform, no block barrier below
-    int* rows = smem + wave * 2 * kWave;
-    float* share = reinterpret_cast<float*>(rows + kWave);
-
-    const int id = lane < p.k1 ? p.ids1[b * p.k1 + lane] : -1;
-    const float w = id >= 0 ? p.w1[b * p.k1 + lane] : 0.0f;
-    float total = w;
-    for (int off = 1; off < kWave; off <<= 1) total += __shfl_xor(total, off);
-    if (!(total > 0.0f)) return;                        // wave-uniform
-    float wsum; bool first;
-    merge_equal_ids_w(id, w, p.k1, lane, 0, wsum, first);
-    const bool keep = id >= 0 && first;
-    const uint64_t kept = __ballot(keep);
-    const int n = __popcll(kept);
-    if (keep) {
-        const int slot = __popcll(kept & lanemask_lt(lane));
-        rows[slot] = id;
-        share[slot] = wsum / total;
-    }
-    __builtin_amdgcn_wave_barrier();
-    for (int64_t d0 = 0; d0 < p.D; d0 += kWave) {
-        const int64_t d = d0 + lane;
-        if (d < p.D) {
-            const float g = p.grad_out[b * p.D + d];
-            for (int e = 0; e < n; ++e) w_atomic_add(p.grad_x + (int64_t)rows[e] * p.D + d, g * share[e]);
-        }
-    }
-}
 
 __global__ __launch_bounds__(512) void wbwd2_kernel(const WBwdParams p) {
     extern __shared__ int smem[];
@@ -155,9 +104,9 @@ hipError_t launch_backward_weighted(const BwdArgs& a, const WeightArgs& w, hipSt
     p.ids1 = a.ids1; p.ids2 = a.ids2;
     p.w1 = w.w1; p.w2 = w.w2; p.grad_x = static_cast<float*>(a.grad_x); p.B = a.B; p.D = a.D; p.k1 = a.k1; p.k2 = a.k2;
     if (!a.ids2) {
-        const int wpb = 4;
-        const unsigned grid = (unsigned)((a.B + wpb - 1) / wpb);
-        hipLaunchKernelGGL(wbwd1_kernel, dim3(grid), dim3(wpb * kWave), sizeof(int) * 2 * kWave * wpb, stream, p);
+        // 1-hop: the unweighted kernel with weight shares instead of 1/count (it merges the rows
+        // the seeds of a workgroup share in LDS, which the hub rows of a skewed graph need)
+        return launch_backward1_weighted(a, w.w1, stream);
     } else {
         const int nw = a.k1 < 8 ? a.k1 : 8;
         const int nq_max = (a.k1 + nw - 1) / nw;

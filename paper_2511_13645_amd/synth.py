@@ -236,6 +236,16 @@ def features(num_rows: int, dim: int, *, dist: str = "normal", dtype: torch.dtyp
     return out
 
 
+def edge_weights(num_edges: int, *, seed: int = 11, device: str = "cpu") -> torch.Tensor:
+    """Per-edge weights for the weighted mean: hashed uniforms in [0, 1), fp32, aligned with `indices`."""
+    out = torch.empty(num_edges, dtype=torch.float32, device=device)
+    step = 1 << 27
+    for e0 in range(0, num_edges, step):
+        e1 = min(num_edges, e0 + step)
+        out[e0:e1] = hash_u01(seed, 0, torch.arange(e0, e1, dtype=torch.int64, device=device)).float()
+    return out
+
+
 def seed_batches(num_nodes: int, batch: int, num_batches: int = 1, *, seed: int = 2) -> torch.Tensor:
     """[num_batches, batch] int32 node ids, each batch uniform without replacement."""
     rng = np.random.default_rng(seed)
