@@ -298,3 +298,32 @@ def test_mid_size_batches_with_roots_of_every_weight(fsa, orc, B, fan, D, bf16):
     a_out, a_h1 = forward_scales(d_x, d1, torch.where(d1[..., None] >= 0, d2, torch.full_like(d2, -1)))
     assert_close(to_f64(g_out), r_out, a_out, TOL[x.dtype], "mid-size replay holes out")
     assert_close(to_f64(g_h1), r_h1, a_h1, TOL[x.dtype], "mid-size replay holes h1")
+
+
+@pytest.mark.parametrize("D,bf16", [(256, False), (260, False), (1024, False), (1028, False), (2048, False), (2052, False),
+                                     (510, False), (1022, False),
+                                     (512, True), (520, True), (2048, True), (2056, True), (4096, True), (4104, True)])
+def test_row_widths_around_the_tile_boundaries(fsa, orc, D, bf16):
+    """Rows of exactly 1, 2, 4, 5, 8 and 9 tiles of 64 lanes (16- and 8-byte chunks): the single-tile
+    gather, both instantiations of the wide-row gather and the fall-back beyond eight tiles, for the
+    1-hop, 2-hop and (through the 3-hop call) slot-mean kernels, with one and with several waves per root."""
+    n = 700
+    indptr, indices = ragged_graph(n, seed=D, max_deg=20, hub_deg=300)
+    rng = np.random.default_rng(D)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    if bf16:
+        x = x.to(torch.bfloat16)
+    seeds = np.concatenate([np.arange(8), rng.integers(0, n, 40)]).astype(np.int32)
+    run_case(fsa, orc, indptr, indices, x, seeds, [7], 3, check_bwd=False, what="tiles 1-hop D=%d" % D)
+    run_case(fsa, orc, indptr, indices, x, seeds, [6, 4], 3, check_bwd=False, what="tiles 2-hop D=%d" % D)
+    big = np.concatenate([seeds] * 90)[:4200]                        # one wave per root
+    run_case(fsa, orc, indptr, indices, x, big, [6, 4], 3, check_bwd=False, what="tiles 2-hop B=4200 D=%d" % D)
+    hx, is_bf16 = host_x(x)
+    ref = orc.sample_mean3_fwd(indptr, indices, hx, seeds, [3, 3, 2], 9, bf16=is_bf16, want_h2=False)
+    r = fsa.fsa_sample_mean3_fwd(torch.from_numpy(indptr).to("cuda:0"), torch.from_numpy(indices).to("cuda:0"), x.to("cuda:0"),
+                                 torch.from_numpy(seeds).to("cuda:0"), [3, 3, 2], 9)
+    torch.cuda.synchronize()
+    scale = orc.mean3_replay_fwd(np.abs(to_f64(x)), ref["ids1"], ref["ids2"], ref["ids3"], want_h2=False)
+    assert_ids_equal(r["ids3"], ref["ids3"], "tiles 3-hop ids3")
+    for k in ("out", "out_h1", "out_m1"):
+        assert_close(to_f64(r[k]), ref[k], scale[k], TOL[x.dtype], "tiles 3-hop %s D=%d" % (k, D))
