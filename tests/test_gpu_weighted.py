@@ -83,7 +83,7 @@ def _run(fsa, orc, indptr, indices, ew, x, seeds, fan, seed, what, check_bwd=Tru
         assert_close(to_f64(gx), r_gx, scale, 1e-5, what + " grad_x")
 
 
-@pytest.mark.parametrize("D", [1, 6, 64, 100, 128, 257, 602])
+@pytest.mark.parametrize("D", [1, 6, 64, 100, 128, 257, 260, 602, 1000, 2052])
 @pytest.mark.parametrize("fan", [[10], [15, 10]])
 def test_weighted_fp32(fsa, orc, D, fan):
     n = 2500
@@ -93,7 +93,7 @@ def test_weighted_fp32(fsa, orc, D, fan):
     _run(fsa, orc, indptr, indices, ew, x, seeds, fan, 77 + D, "weighted fp32 D=%d fan=%s" % (D, fan))
 
 
-@pytest.mark.parametrize("D", [3, 128, 200])
+@pytest.mark.parametrize("D", [3, 128, 200, 520, 2056])
 @pytest.mark.parametrize("fan", [[15], [25, 10], [3, 33]])
 def test_weighted_bf16_wide_indptr(fsa, orc, D, fan):
     n = 2000
