@@ -176,6 +176,26 @@ def test_ceilings_library_builds_and_exports_its_entry_point():
     assert C.fsa_ceilings_measure(28, None) == -1
 
 
+def test_binding_refuses_host_tensors_and_wrong_types(fsa):
+    """The Python layer only marshals: tensors that are not on the GPU, not contiguous or of the wrong type are
+    refused before the library is called (no CPU fallback exists)."""
+    import torch
+    indptr = torch.zeros(5, dtype=torch.int32)
+    indices = torch.zeros(3, dtype=torch.int32)
+    x = torch.zeros((4, 8))
+    seeds = torch.zeros(2, dtype=torch.int32)
+    with pytest.raises(ValueError, match="GPU"):
+        fsa.fsa_sample_mean_fwd(indptr, indices, x, seeds, [2], 0)
+    with pytest.raises(ValueError, match="GPU"):
+        fsa.fsa_mean_replay_fwd(x, torch.zeros((2, 2), dtype=torch.int32))
+    with pytest.raises(ValueError, match="GPU"):
+        fsa.fsa_mean_bwd(torch.zeros((2, 8)), torch.zeros((2, 2), dtype=torch.int32), grad_x=x)
+    with pytest.raises(ValueError, match="GPU"):
+        fsa.fsa_sample_mean3_fwd(indptr, indices, x, seeds, [2, 2, 2], 0)
+    with pytest.raises(ValueError):
+        fsa.fsa_sample_mean3_fwd(indptr, indices, x, seeds, [2, 2], 0)
+
+
 def test_binding_fails_loudly_without_library(fsa, monkeypatch):
     monkeypatch.setattr(fsa, "_lib", None)
     monkeypatch.setattr(fsa, "LIB_PATH", "/nonexistent/libfsa_hip.so")
