@@ -140,3 +140,24 @@ def test_weighted_large_shape_forward_backward(fsa, orc):
     seeds = synth.seed_batches(g.num_nodes, 2048, 1, seed=2)[0]
     _run(fsa, orc, g.indptr.cpu().numpy(), g.indices.cpu().numpy(), ew.cpu().numpy(), w.x.cpu(), seeds.numpy(),
          [15, 10], 0, "weighted products@0.05")
+
+
+@pytest.mark.parametrize("n_targets,B", [(3, 700), (100, 4096), (1000, 20000)])
+def test_weighted_backward_with_heavily_shared_rows(fsa, orc, n_targets, B):
+    """Every edge points into a small set of nodes, so the seeds of a workgroup keep hitting the
+    same rows: the 1-hop weighted backward sums them in LDS (weight shares instead of 1/count),
+    also with zero weights, seeds whose weights sum to zero and parallel edges."""
+    rng = np.random.default_rng(n_targets)
+    n, D, k = 30000, 96, 15
+    deg = rng.integers(0, 40, size=n)
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+    hot = rng.permutation(n)[:n_targets]
+    p = 1.0 / np.arange(1, n_targets + 1) ** 1.2
+    indices = hot[rng.choice(n_targets, size=int(indptr[-1]), p=p / p.sum())].astype(np.int32)
+    ew = rng.random(indices.size).astype(np.float32)
+    ew[rng.random(indices.size) < 0.1] = 0.0
+    for v in range(0, n, 97):                                   # whole rows of zero weight
+        ew[indptr[v]:indptr[v + 1]] = 0.0
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    seeds = np.concatenate([np.arange(0, n, 97)[:50], rng.integers(0, n, B - 50)]).astype(np.int32)
+    _run(fsa, orc, indptr, indices, ew, x, seeds, [k], 3, "weighted shared rows %d" % n_targets)
