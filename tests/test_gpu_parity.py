@@ -327,3 +327,29 @@ def test_row_widths_around_the_tile_boundaries(fsa, orc, D, bf16):
     assert_ids_equal(r["ids3"], ref["ids3"], "tiles 3-hop ids3")
     for k in ("out", "out_h1", "out_m1"):
         assert_close(to_f64(r[k]), ref[k], scale[k], TOL[x.dtype], "tiles 3-hop %s D=%d" % (k, D))
+
+
+def test_maximum_fanouts_with_one_wave_per_root(fsa, orc):
+    """Fanouts 64/64 at a batch size that gives every root a single wave: 4096 leaf slots per
+    wave in LDS (more than 64 KB per workgroup).  The oracle checks the first 64 seeds (results do
+    not depend on the rest of the batch); the backward runs over the whole batch."""
+    n, D, B, fan = 3000, 32, 4100, [64, 64]
+    indptr, indices = ragged_graph(n, seed=5, max_deg=200, hub_deg=4000)
+    rng = np.random.default_rng(0)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    seeds = rng.integers(0, n, B).astype(np.int32)
+    ref = orc.sample_mean_fwd(indptr, indices, x.numpy(), seeds[:64], fan, 3)
+    out, h1, ids1, ids2 = fsa.fsa_sample_mean_fwd(torch.from_numpy(indptr).cuda(), torch.from_numpy(indices).cuda(), x.cuda(),
+                                                  torch.from_numpy(seeds).cuda(), fan, 3)
+    torch.cuda.synchronize()
+    assert_ids_equal(ids1[:64], ref[2], "ids1")
+    assert_ids_equal(ids2[:64], ref[3], "ids2")
+    a_out, a_h1 = forward_scales(x.cuda(), ids1[:64], ids2[:64])
+    assert_close(to_f64(out[:64]), ref[0], a_out, 1e-5, "out")
+    assert_close(to_f64(h1[:64]), ref[1], a_h1, 1e-5, "out_h1")
+    g = torch.from_numpy(rng.standard_normal((B, D)).astype(np.float32)).cuda()
+    gx = fsa.fsa_mean_bwd(g, ids1, ids2, grad_x=torch.zeros((n, D), device="cuda:0"))
+    torch.cuda.synchronize()
+    want = orc.mean_bwd(to_f64(g), ids1.cpu().numpy(), ids2.cpu().numpy(), num_nodes=n)
+    mag = orc.mean_bwd(np.abs(to_f64(g)), ids1.cpu().numpy(), ids2.cpu().numpy(), num_nodes=n)
+    assert_close(to_f64(gx), want, mag, 1e-5, "grad_x")
