@@ -422,7 +422,6 @@ int orc_wmean_bwd(const double* grad_out, const double* grad_h1,
     return 0;
 }
 
-// Round-to-nearest-even from double straight to the 8-bit significand of bfloat16.
 // ---- three hops (the nested mean of Sec. 3.2 taken one level deeper) -------------------
 
 // Prop. 1 for three levels of saved IDs: every mean is the plain mean of the named rows, and

@@ -3,6 +3,10 @@
 #include "../../include/fsa.h"
 #include "fsa_internal.h"
 
+#ifdef FSA_TRACE
+namespace fsa { long long* g_trace = nullptr; }
+#endif
+
 namespace {
 
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -375,6 +379,11 @@ int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad
     return FSA_OK;
 }
 
+
+#ifdef FSA_TRACE
+// Debug builds only: device buffer [B][4] of int64 that the 2-hop forward stamps (NULL = off).
+void fsa_debug_set_trace(void* device_buffer) { fsa::g_trace = static_cast<long long*>(device_buffer); }
+#endif
 
 const char* fsa_status_string(int status) {
     switch (status) {

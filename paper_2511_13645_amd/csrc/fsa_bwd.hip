@@ -11,7 +11,6 @@
 #include "fsa_device.hip.h"
 #include "fsa_internal.h"
 
-#include <cstdlib>
 #include <type_traits>
 
 namespace fsa {
@@ -422,11 +421,6 @@ hipError_t launch_deep_grad(const float* grad_out, const float* grad_h1, const i
     return hipGetLastError();
 }
 
-static int env_int(const char* name, int fallback) {
-    const char* v = std::getenv(name);
-    return v ? std::atoi(v) : fallback;
-}
-
 template <typename GT, typename XG, bool WEIGHTED>
 static hipError_t launch_bwd1(const BwdArgs& a, const BwdParams& p, hipStream_t stream) {
     // Workgroups of 16 waves: the rows the seeds of a workgroup share are merged in LDS, so the
@@ -434,8 +428,8 @@ static hipError_t launch_bwd1(const BwdArgs& a, const BwdParams& p, hipStream_t 
     // through them side by side.  Seeds per wave grow with the batch so that the launch keeps
     // a few hundred workgroups (measured on the KG shape, B = 1024 .. 262144: 14.7 us at
     // B=4096 against 20.4 us with 4-wave workgroups, 84 against 136 us at B=65536).
-    static const int forced_spw = env_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
-    static const int forced_nw = env_int("FSA_BWD1_WAVES", 0);
+    const int forced_spw = tune_int("FSA_BWD1_SEEDS_PER_WAVE", 0);
+    const int forced_nw = tune_int("FSA_BWD1_WAVES", 0);
     const int nw = (forced_nw >= 1 && forced_nw <= 16) ? forced_nw : 16;
     int spw = 1;
     while (spw < 16 && a.B / ((int64_t)nw * spw * 2) >= 256) spw *= 2;
@@ -444,8 +438,7 @@ static hipError_t launch_bwd1(const BwdArgs& a, const BwdParams& p, hipStream_t 
     const size_t lds_fixed = sizeof(int) * (3 * kHotBuckets + 2 + kHotRowsMax + nw * 3 * kWave);
     int hot_rows = (int)((65536 - lds_fixed) / (sizeof(float) * (size_t)a.D));
     if (hot_rows > kHotRowsMax) hot_rows = kHotRowsMax;
-    static const int no_hot = env_int("FSA_BWD1_NO_HOT", 0);
-    if (no_hot) hot_rows = 0;
+    if (tune_int("FSA_BWD1_NO_HOT", 0)) hot_rows = 0;
     const unsigned grid = (unsigned)((a.B + nw * spw - 1) / (nw * spw));
     const size_t lds = lds_fixed + sizeof(float) * (size_t)hot_rows * a.D;
     hipLaunchKernelGGL((bwd1_kernel<GT, XG, WEIGHTED>), dim3(grid), dim3(nw * kWave), lds, stream, p, spw, hot_rows);
@@ -457,7 +450,7 @@ static hipError_t launch_backward_typed(const BwdArgs& a, const BwdParams& p, hi
     if (!a.ids2) {
         return launch_bwd1<GT, XG, false>(a, p, stream);
     } else {
-        static const int forced = env_int("FSA_BWD2_WAVES", 0);
+        const int forced = tune_int("FSA_BWD2_WAVES", 0);
         int nw = (forced >= 1 && forced <= 8) ? forced : (a.k1 < 8 ? a.k1 : 8);
         const int nq_max = (a.k1 + nw - 1) / nw;
         const size_t lds = sizeof(int) * ((size_t)nw * (2 * nq_max * a.k2 + 2 * nq_max) + nw);

@@ -6,9 +6,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#ifndef FSA_DUP_CHUNK
-#define FSA_DUP_CHUNK 4      // shuffles issued together in the duplicate test
-#endif
+#include "fsa_layout.h"
 
 namespace fsa {
 
@@ -42,7 +40,8 @@ __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane
 //
 // The wave is cut into segments of k consecutive lanes starting at seg_base; lane
 // seg_base+li runs step li of its segment's row.  All 64 lanes must call this together
-// (it shuffles and ballots); lanes without a row pass active=false.
+// (it ballots and goes through the wave's LDS draw strip); lanes without a row pass
+// active=false.
 //
 // Sequential Floyd inserts t_i unless it is already chosen, else J_i = deg-k+i.  Whatever
 // happens at step m, t_m is in the set afterwards, and J_m is in it exactly when step m
@@ -55,30 +54,39 @@ __device__ __forceinline__ uint64_t lanemask_lt(int lane) { return (1ull << lane
 // Returns this lane's position inside the row (0-based), or -1 for an unused slot.
 // deg <= k keeps the whole row in CSR order (Sec. 3.2: t = min(k, |N(v)|)).
 // ---------------------------------------------------------------------------------------
-// The draw of Floyd step li for a row of length deg (only meaningful when deg > k).
-__device__ __forceinline__ uint32_t floyd_draw(uint64_t seed, uint32_t node, uint32_t hop, int k,
-                                               int li, int64_t deg) {
-    const uint32_t r = philox4x32_10_word0(node, hop, (uint32_t)li, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
-    return __umulhi(r, (uint32_t)(deg - k) + (uint32_t)li + 1u);    // uniform in [0, J_li]
+// The generator word of Floyd step li of a node's row: a pure function of (seed, node, hop,
+// step), so it can be drawn before the row's extent is known.
+__device__ __forceinline__ uint32_t floyd_word(uint64_t seed, uint32_t node, uint32_t hop, int li) {
+    return philox4x32_10_word0(node, hop, (uint32_t)li, 0u, (uint32_t)seed, (uint32_t)(seed >> 32));
 }
 
-// Turn the draws of a segment into positions (see above).  `t` is this lane's draw.
+// The draw of step li for a row of length deg (only meaningful when deg > k): uniform in [0, J_li].
+__device__ __forceinline__ uint32_t floyd_bound(uint32_t word, int k, int li, int64_t deg) {
+    return __umulhi(word, (uint32_t)(deg - k) + (uint32_t)li + 1u);
+}
+
+// Turn the draws of a segment into positions (see above).  `t` is this lane's draw; `draws`
+// is the wave's LDS strip of kDrawStripInts ints (free to reuse when this returns).
 __device__ __forceinline__ int64_t floyd_resolve(uint32_t t, int k, int li, int seg_base, int64_t deg,
-                                                 bool active, int lane) {
+                                                 bool active, int lane, int* draws) {
     const bool floyd = active && deg > (int64_t)k;
     const uint32_t base = floyd ? (uint32_t)(deg - k) : 0u;          // J_i = base + li
     bool collided = false;
     if (__any(floyd)) {                                              // wave-uniform
-        // duplicate of an earlier draw of the same segment; shuffles issued a few at a time so
-        // that their latencies overlap (steps beyond k or beyond li never match the m < li test)
+        // duplicate of an earlier draw of the same segment: every lane publishes its draw and
+        // reads its segment back four entries at a time (entries at or beyond li never match
+        // the m < li test, so the overshoot past the segment is harmless)
+        draws[lane] = (int)t;
+        __builtin_amdgcn_wave_barrier();
+        const int* seg = draws + seg_base;
         bool dup_earlier = false;
-        for (int m0 = 0; m0 < k; m0 += FSA_DUP_CHUNK) {
-            uint32_t tm[FSA_DUP_CHUNK];
-#pragma unroll
-            for (int j = 0; j < FSA_DUP_CHUNK; ++j) tm[j] = (uint32_t)__shfl((int)t, seg_base + m0 + j);
-#pragma unroll
-            for (int j = 0; j < FSA_DUP_CHUNK; ++j) dup_earlier = dup_earlier || (m0 + j < li && tm[j] == t);
+        for (int m0 = 0; m0 < k; m0 += 4) {
+            const uint32_t t0 = (uint32_t)seg[m0], t1 = (uint32_t)seg[m0 + 1];
+            const uint32_t t2 = (uint32_t)seg[m0 + 2], t3 = (uint32_t)seg[m0 + 3];
+            dup_earlier = dup_earlier || (m0 < li && t0 == t) || (m0 + 1 < li && t1 == t) ||
+                          (m0 + 2 < li && t2 == t) || (m0 + 3 < li && t3 == t);
         }
+        __builtin_amdgcn_wave_barrier();
         const bool hits_J = floyd && t >= base && (t - base) < (uint32_t)li;
         const int dep_lane = seg_base + (int)(t - base);
         // Least fixed point of  c_i = dup_i | (hits_J_i & c_dep(i)):  dependencies only point to
@@ -96,12 +104,18 @@ __device__ __forceinline__ int64_t floyd_resolve(uint32_t t, int k, int li, int 
     return (active && (int64_t)li < deg) ? (int64_t)li : -1;
 }
 
-__device__ __forceinline__ int64_t floyd_position(uint64_t seed, uint32_t node, uint32_t hop,
-                                                  int k, int li, int seg_base, int64_t deg,
-                                                  bool active, int lane) {
-    uint32_t t = 0u;
-    if (__any(active && deg > (int64_t)k)) t = floyd_draw(seed, node, hop, k, li, deg);   // wave-uniform
-    return floyd_resolve(t, k, li, seg_base, deg, active, lane);
+// Inclusive prefix sum over the 64 lanes: four row-shift steps inside each row of 16 lanes,
+// then the totals of the lower rows are added to the rows above them.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1, lanes shifted in read 0
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    const int r0 = __builtin_amdgcn_readlane(v, 15);
+    const int r1 = __builtin_amdgcn_readlane(v, 31);
+    const int r2 = __builtin_amdgcn_readlane(v, 47);
+    const int row = lane >> 4;
+    return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
 template <typename IT>
@@ -256,27 +270,34 @@ template <int VB> struct Chunk<f16_t, VB> {
 };
 
 // Sum the chunk at byte offset `chunk_off` of rows ids[first], ids[first+stride], ... (index
-// below count) into acc, in that order.  Up to UNROLL row loads are issued before the first
-// add so that their latencies overlap.  `ids` lives in LDS.
-template <typename XT, int VB, int UNROLL>
+// below count) into acc, in that order; WEIGHTED multiplies each row by wts[i] and adds the
+// weights into wsum.  Up to UNROLL row loads are issued before the first add so that their
+// latencies overlap.  `ids` and `wts` live in LDS.
+template <typename XT, int VB, int UNROLL, bool WEIGHTED>
 __device__ __forceinline__ void sum_row_chunks(const char* __restrict__ x, int64_t row_bytes,
-                                               int64_t chunk_off, const int* ids, int first,
+                                               int64_t chunk_off, const int* ids, const float* wts, int first,
                                                int count, int stride,
-                                               float (&acc)[Chunk<XT, VB>::VE]) {
+                                               float (&acc)[Chunk<XT, VB>::VE], float& wsum) {
     using C = Chunk<XT, VB>;
     using Raw = typename C::Raw;
     for (int i0 = first; i0 < count; i0 += stride * UNROLL) {
         Raw r[UNROLL];
+        float wr[UNROLL];
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int i = i0 + u * stride;
-            if (i < count)
+            if (i < count) {
+                if constexpr (WEIGHTED) wr[u] = wts[i];
                 r[u] = *reinterpret_cast<const Raw*>(x + (int64_t)ids[i] * row_bytes + chunk_off);
+            }
         }
 #pragma unroll
         for (int u = 0; u < UNROLL; ++u) {
             const int i = i0 + u * stride;
-            if (i < count) C::add(acc, r[u]);
+            if (i < count) {
+                if constexpr (WEIGHTED) { C::fma(acc, r[u], wr[u]); wsum += wr[u]; }
+                else C::add(acc, r[u]);
+            }
         }
     }
 }

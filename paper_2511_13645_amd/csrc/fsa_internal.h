@@ -4,7 +4,28 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#ifdef FSA_TUNING
+#include <cstdlib>
+#endif
+
 namespace fsa {
+
+// Launch-shape overrides for sweeps.  Only a library built with -DFSA_TUNING (a separately
+// named build that is never shipped) reads the environment; the product returns the default.
+#ifdef FSA_TUNING
+inline int tune_int(const char* name, int fallback) {
+    const char* v = std::getenv(name);
+    return v ? std::atoi(v) : fallback;
+}
+#else
+constexpr int tune_int(const char*, int fallback) { return fallback; }
+#endif
+
+#ifdef FSA_TRACE
+// Debug builds only (-DFSA_TRACE): per-root time stamps of the 2-hop forward go to this
+// device buffer, set through fsa_debug_set_trace().
+extern long long* g_trace;
+#endif
 
 // How a feature row is cut into per-lane chunks and how lanes are grouped over rows.
 struct RowGeom {
