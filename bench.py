@@ -27,6 +27,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# Bandwidth / atomic-rate microbenchmarks of `--ceilings`: a measurement aid of this script, not
+# part of the product library.
+CEILINGS_SRC = os.path.join(ROOT, "bench_ceilings.hip")
+CEILINGS_LIB = os.path.join(ROOT, "libbench_ceilings.so")
+
+
+def build_ceilings(verbose: bool = False) -> str:
+    """Compile bench_ceilings.hip for gfx950 into libbench_ceilings.so (next to this script)."""
+    import subprocess
+    from paper_2511_13645_amd import build as hip_build
+    tmp = CEILINGS_LIB + ".tmp.%d" % os.getpid()
+    cmd = [hip_build.hipcc(), *hip_build.HIPCC_FLAGS, "-shared", "-o", tmp, CEILINGS_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    os.replace(tmp, CEILINGS_LIB)
+    return CEILINGS_LIB
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -45,6 +63,155 @@ def algorithmic_bytes(leaf_rows, hop1_rows, B, k1, k2, D, elem, iptr, emit_ids=T
     if emit_ids:
         b += 4 * B * (k1 + k1 * k2)
     return b
+
+
+def csrc_hash():
+    """SHA-256 over the kernel sources the library is built from (file names and bytes, sorted)."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2511_13645_amd", "csrc")
+    for fn in sorted(os.listdir(d)):
+        if fn.endswith((".hip", ".h")):
+            h.update(fn.encode())
+            h.update(open(os.path.join(d, fn), "rb").read())
+    return h.hexdigest()
+
+
+def committed_traffic(workload):
+    """HBM bytes per launch from the committed counter runs -- only while the kernel sources are
+    the ones those runs were made with; otherwise None (the figure would be stale)."""
+    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % workload)
+    try:
+        t = json.load(open(tpath))
+    except Exception:
+        return None
+    if t.get("csrc_sha256") != csrc_hash():
+        log("[bench] %s was measured on other kernel sources: roofline.traffic = null" % os.path.basename(tpath))
+        return None
+    return t.get("hbm_bytes_per_launch")
+
+
+def traffic_from_counters(args):
+    """--traffic-from: turn two rocprofv3 --pmc counter CSVs (FETCH_SIZE run, WRITE_SIZE run; both made
+    with --calibrate-copy) into profiles/traffic_<workload>.json, stamped with the source hash."""
+    import csv
+    fetch_csv, write_csv = args.traffic_from
+
+    def mean_kib(path, counter, needle):
+        v = [float(r["Counter_Value"]) for r in csv.DictReader(open(path))
+             if r["Counter_Name"] == counter and needle in r["Kernel_Name"]]
+        if not v:
+            raise RuntimeError("%s: no %s rows for a kernel named *%s*" % (path, counter, needle))
+        return sum(v) / len(v), len(v)
+    gib_kib = float(1 << 20)                     # the calibration copy moves 1 GiB each way
+    f_copy, _ = mean_kib(fetch_csv, "FETCH_SIZE", "copyBuffer")
+    w_copy, _ = mean_kib(write_csv, "WRITE_SIZE", "copyBuffer")
+    f_k, n_f = mean_kib(fetch_csv, "FETCH_SIZE", args.traffic_kernel)
+    w_k, n_w = mean_kib(write_csv, "WRITE_SIZE", args.traffic_kernel)
+    f_scale, w_scale = gib_kib / f_copy, gib_kib / w_copy
+    out = {"hbm_bytes_per_launch": int(round((f_k * f_scale + w_k * w_scale) * 1024)),
+           "fetch_kib": f_k, "fetch_scale": f_scale, "write_kib": w_k, "write_scale": w_scale,
+           "dispatches": [n_f, n_w], "kernel": args.traffic_kernel, "workload": args.workload,
+           "csrc_sha256": csrc_hash()}
+    path = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
+    json.dump(out, open(path, "w"), indent=1)
+    print(json.dumps(out))
+    return 0
+
+
+def measure_paths(L, binding, synth, torch, w, B, dev, n_launch=20, replay=True, backward=True):
+    """Forward with ID and per-slot emission over `n_launch` fresh seed batches, then the replay forward
+    and (fp32 tables) the backward on the IDs of those batches: launch duration by HIP events around
+    back-to-back launches, algorithmic bytes from the actual counts, fraction of the HBM peak."""
+    g, x = w.graph, w.x
+    fan = list(w.fanouts)
+    hops = len(fan)
+    k1 = fan[0]
+    k2 = fan[1] if hops == 2 else 0
+    N, D = x.shape
+    elem, iptr = x.element_size(), g.indptr.element_size()
+    if B > N:
+        return None
+    x_code = {torch.float32: binding.FSA_F32, torch.bfloat16: binding.FSA_BF16, torch.float16: binding.FSA_F16}[x.dtype]
+    n_all = n_launch + 2
+    seeds = synth.seed_batches(N, B, n_all, seed=6).to(dev)
+    out = torch.empty((B, D), dtype=x.dtype, device=dev)
+    out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev) if hops == 2 else None
+    ids1 = torch.empty((n_all, B, k1), dtype=torch.int32, device=dev)
+    ids2 = torch.empty((n_all, B, k1, k2), dtype=torch.int32, device=dev) if hops == 2 else None
+    fan_host = (ctypes.c_int32 * hops)(*fan)
+    stream = torch.cuda.current_stream().cuda_stream
+    h1_ptr = None if out_h1 is None else out_h1.data_ptr()
+    # pointers are looked up once: a launch of a few microseconds must not wait for the host
+    seed_p = [seeds[i].data_ptr() for i in range(n_all)]
+    id1_p = [ids1[i].data_ptr() for i in range(n_all)]
+    id2_p = [ids2[i].data_ptr() if hops == 2 else None for i in range(n_all)]
+    i2 = id2_p.__getitem__
+    p_indptr, p_indices, p_x, p_out = g.indptr.data_ptr(), g.indices.data_ptr(), x.data_ptr(), out.data_ptr()
+    it_code = binding.FSA_I64 if iptr == 8 else binding.FSA_I32
+    fan_p = ctypes.cast(fan_host, ctypes.c_void_p)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        for i in range(2):
+            fn(i)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(2, n_all):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_launch
+
+    def fwd(i):
+        rc = L.fsa_sample_mean_fwd(p_indptr, it_code, p_indices, N, p_x, x_code, D, seed_p[i], B, fan_p, hops,
+                                   w.sampler_seed, p_out, h1_ptr, id1_p[i], i2(i), stream)
+        if rc != 0:
+            raise RuntimeError("fsa_sample_mean_fwd -> %d" % rc)
+    f_ms = timed(fwd)
+    if hops == 2:
+        leaf = int((ids2[2:] >= 0).sum().item()) / n_launch
+        hop1 = int((ids1[2:] >= 0).sum().item()) / n_launch
+        f_alg = algorithmic_bytes(leaf, hop1, B, k1, k2, D, elem, iptr)
+    else:
+        leaf = int((ids1[2:] >= 0).sum().item()) / n_launch
+        f_alg = leaf * (D * elem + 4) + B * (2 * iptr + 4 + D * elem) + 4 * B * k1
+
+    def block(ms, alg, **more):
+        gbps = alg / (ms * 1e-3) / 1e9
+        return {"launch_us": ms * 1e3, "rows_per_s": leaf / (ms * 1e-3), "algorithmic_bytes_per_launch": alg,
+                "hbm_gbps": gbps, "frac": gbps / HBM_PEAK_GBPS, **more}
+    r = {"workload": w.name, "dtype": str(x.dtype).split(".")[1], "D": D, "fanouts": fan, "global_batch": B,
+         "rows_per_launch": leaf, "forward": block(f_ms, f_alg)}
+    if replay:
+        def rep(i):
+            rc = L.fsa_mean_replay_fwd(p_x, x_code, D, N, id1_p[i], i2(i), B, k1, k2, p_out, h1_ptr, stream)
+            if rc != 0:
+                raise RuntimeError("fsa_mean_replay_fwd -> %d" % rc)
+        r_ms = timed(rep)
+        # saved IDs read instead of the graph; the same rows and outputs
+        r_alg = leaf * D * elem + 4 * B * (k1 + k1 * k2) + B * D * elem + (B * k1 * D * elem if hops == 2 else 0)
+        r["replay_forward"] = block(r_ms, r_alg)
+    if backward and x.dtype == torch.float32:
+        g_out = synth.upstream_grad((B, D), seed=3, device=dev)
+        g_h1 = synth.upstream_grad((B, k1, D), seed=4, device=dev) if hops == 2 else None
+        grad_x = torch.zeros((N, D), dtype=torch.float32, device=dev)
+        p_go, p_gh, p_gx = g_out.data_ptr(), None if g_h1 is None else g_h1.data_ptr(), grad_x.data_ptr()
+
+        def bwd(i):
+            rc = L.fsa_mean_bwd(p_go, p_gh, id1_p[i], i2(i), B, k1, k2, D, p_gx, N, stream)
+            if rc != 0:
+                raise RuntimeError("fsa_mean_bwd -> %d" % rc)
+        b_ms = timed(bwd)                       # accumulates on; zero-filling grad_x is the caller's
+        payload = leaf * D * 4
+        # every leaf row of grad_x read and written once, its ID, the upstream gradient rows
+        b_alg = 2 * payload + 4 * leaf + B * D * 4 + (B * k1 * D * 4 if hops == 2 else 0)
+        r["backward"] = block(b_ms, b_alg, atomic_payload_gbps=payload / (b_ms * 1e-3) / 1e9,
+                              vs_forward=b_ms / f_ms)
+        del g_out, g_h1, grad_x
+    log("[bench] %s B=%d %s: %s" % (w.name, B, r["dtype"], ", ".join(
+        "%s %.1f us (%.3f)" % (k, r[k]["launch_us"], r[k]["frac"]) for k in ("forward", "replay_forward", "backward") if k in r)))
+    return r
 
 
 def load_or_make_workload(name, scale, cache, dev):
@@ -229,7 +396,15 @@ def main() -> int:
                          "(streaming read, copy, random row gather, row atomics, row stores); adds `ceilings`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a 1 GiB device-to-device copy first, so a counter run can scale its byte counters")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the fp32-table variant of the headline shape and the other workload shapes "
+                         "(`fp32_variant`, `workloads`), which the default run of the citation workload adds")
+    ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="no GPU work: write profiles/traffic_<workload>.json from two rocprofv3 --pmc counter CSVs")
+    ap.add_argument("--traffic-kernel", default="fwd2_kernel", help="kernel name fragment for --traffic-from")
     args = ap.parse_args()
+    if args.traffic_from:
+        return traffic_from_counters(args)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU by scope (no sharding, no collectives); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -255,10 +430,9 @@ def main() -> int:
 
     ceilings = None
     if args.ceilings:
-        from paper_2511_13645_amd import build as hip_build
-        if not os.path.exists(hip_build.CEILINGS_LIB):
-            raise RuntimeError("libfsa_ceilings.so missing: build it with __graft_entry__.build()")
-        C = ctypes.CDLL(hip_build.CEILINGS_LIB)
+        if not os.path.exists(CEILINGS_LIB):
+            raise RuntimeError("%s missing: build it with __graft_entry__.build()" % CEILINGS_LIB)
+        C = ctypes.CDLL(CEILINGS_LIB)
         C.fsa_ceilings_measure.argtypes = [ctypes.c_int, ctypes.c_void_p]
         C.fsa_ceilings_measure.restype = ctypes.c_int
         vals = (ctypes.c_double * 7)()
@@ -379,13 +553,9 @@ def main() -> int:
         (ms_per_step * 1e3, kern_ms * 1e3, leaf_rows / steps, alg_per_launch / 1e6))
 
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_%s.json" % w.name)
     # the committed counter runs cover the workload as named (its own batch, table type, emission on)
-    if os.path.exists(tpath) and not args.batch and not args.feature_dtype and emit and args.scale == 1.0:
-        try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+    if not args.batch and not args.feature_dtype and emit and args.scale == 1.0:
+        traffic = committed_traffic(w.name)
 
     other_paths = None
     if args.paths and emit:
@@ -611,14 +781,38 @@ def main() -> int:
             cpu["all_cores"] = {"value": rows_mt / spent_mt, "unit": "rows/s", "cores": n_thr,
                                 "sample": "%d batches in %.1f s, one slice of seeds per thread" % (batches_mt, spent_mt)}
 
+    # the claims about the other shapes, under the same clock as the headline: the same graph with
+    # the table widened to fp32 (D = 128, 56.8 GB) at the headline batch and at the saturating one,
+    # then the product, social and KG shapes, each with forward, replay forward and backward
+    workload_text = ("%s: N=%d, E=%d, D=%d %s, %s indptr, B=%d, fanouts=%s, emit_ids=%s, scale=%g" %
+                     (w.name, N, g.num_edges, D, "bf16" if elem == 2 else "fp32",
+                      "int64" if iptr == 8 else "int32", B, fan, emit, args.scale))
+    x_is_bf16 = x.dtype == torch.bfloat16
+    fp32_variant = None
+    workloads = None
+    if (not args.no_extras and w.name == "citation" and not args.batch and not args.feature_dtype
+            and args.scale == 1.0 and emit):
+        del seeds, out, out_h1, ids1, ids2
+        w32 = synth.Workload(w.name, g, x.float(), B, tuple(fan), w.sampler_seed)
+        fp32_variant = [measure_paths(L, binding, synth, torch, w32, B, dev),
+                        measure_paths(L, binding, synth, torch, w32, 65536, dev, replay=False, backward=False)]
+        del w32, w, g, x
+        torch.cuda.empty_cache()
+        workloads = []
+        for name in ("products", "social", "kg"):
+            wk = synth.make_workload(name, device=dev)
+            workloads.append(measure_paths(L, binding, synth, torch, wk, wk.batch, dev))
+            if name == "kg":
+                workloads.append(measure_paths(L, binding, synth, torch, wk, 65536, dev))
+            del wk
+            torch.cuda.empty_cache()
+
     line = {
         "metric": "sampled neighbor rows aggregated/sec + achieved HBM GB/s, fanout %s D=%d" % ("/".join(map(str, fan)), D),
         "value": rows_per_s, "unit": "rows/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if x.dtype == torch.bfloat16 else "f32", "data": "synthetic",
-        "config": {"workload": "%s: N=%d, E=%d, D=%d %s, %s indptr, B=%d, fanouts=%s, emit_ids=%s, scale=%g" %
-                               (w.name, N, g.num_edges, D, "bf16" if elem == 2 else "fp32",
-                                "int64" if iptr == 8 else "int32", B, fan, emit, args.scale),
+        "dtype": "bf16" if x_is_bf16 else "f32", "data": "synthetic",
+        "config": {"workload": workload_text,
                    "global_batch": B, "rows_per_launch": leaf_rows / steps,
                    "algorithmic_bytes_per_launch": alg_per_launch},
         "hbm_gbps": achieved,
@@ -628,6 +822,8 @@ def main() -> int:
                      "launch_us_event_pairs": pct},
         "cpu_baseline": cpu,
         "saturated": saturated,
+        "fp32_variant": fp32_variant,
+        "workloads": workloads,
         "other_paths": other_paths,
         "batch_sweep": batch_sweep,
         "ceilings": ceilings,

@@ -1,7 +1,7 @@
 // Measurement aid, not part of the product API: what this GPU sustains on the plain access
 // patterns the kernels are made of, so that their achieved rates can be read against a
 // measured ceiling next to the nominal 8 TB/s.  Built as a library of its own
-// (libfsa_ceilings.so) and called only by the benchmark (bench.py --ceilings).
+// (libbench_ceilings.so) and called only by the benchmark (bench.py --ceilings).
 //   0  streaming read of the whole table, 16-byte loads
 //   1  device copy of 4 GB (bytes read + bytes written)
 //   2  gather of 256-byte rows at random places of the table, 16 lanes x 16 B per row,

@@ -34,8 +34,19 @@
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL = default stream)
  *     and return without synchronising.  Outputs are valid once the stream has drained.
  *   - Return value: FSA_OK or a negative fsa_status.  Arguments are validated on the host
- *     before anything is launched; on error nothing is launched and no output is written.
+ *     before anything is launched: a validation error (every status but FSA_ERR_HIP) means
+ *     nothing was launched and no output was written.  FSA_ERR_HIP means the HIP runtime
+ *     refused a launch; an entry point that is a chain of launches (the layer-wise and
+ *     three-hop calls) may then already have enqueued its earlier ones.  Every entry point
+ *     discards an error that an earlier HIP call of the caller left pending before it
+ *     launches, so FSA_ERR_HIP always refers to this call.  FSA_ERR_ARG is also returned when
+ *     the fanouts need more LDS than the device offers.
  *     B == 0 returns FSA_OK without a launch (batch-sized arrays may then be NULL).
+ *   - The library reads no environment variable and keeps no state between calls.
+ *   - grad_x (backward entry points) must be ordinary coarse-grained device memory
+ *     (hipMalloc; not fine-grained, host-mapped or managed memory): the kernels add into it
+ *     with hardware floating-point atomics resolved in the device's L2, which other kinds of
+ *     memory do not honour.
  *   - Node IDs in `seeds`, `indices`, `ids1`, `ids2` must lie in [0, num_nodes) (or be
  *     negative padding in ids1/ids2); this is not checked on the device.  Rows must be
  *     shorter than 2^31 entries.
@@ -207,6 +218,7 @@ int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad
                   const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
                   int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
                   float* grad_x, int64_t num_nodes, float* work, void* stream);
+
 
 /*
  * Weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted numerators

@@ -341,6 +341,7 @@ int orc_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
     const int32_t k1 = fanouts[0];
     const int32_t k2 = (num_hops == 2) ? fanouts[1] : 0;
     if (k1 <= 0 || (num_hops == 2 && k2 <= 0)) return -2;
+    if (B == 0) return 0;                                     // an empty batch: nothing to sample or write
     // sample IDs and pick up the weight of every sampled edge slot, then average as in replay
     std::vector<int32_t> U(static_cast<size_t>(B) * k1, -1), W;
     std::vector<float> A(static_cast<size_t>(B) * k1, 0.0f), Wt;
@@ -364,11 +365,12 @@ int orc_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
             for (int32_t i = 0; i < c2; ++i) Wt[(b * k1 + j) * k2 + i] = edge_weight[s1 + pos[i]];
         }
     }
-    if (ids1) std::memcpy(ids1, U.data(), sizeof(int32_t) * U.size());
-    if (w1) std::memcpy(w1, A.data(), sizeof(float) * A.size());
+    // (an empty batch has nothing to copy: memcpy must not be handed the empty vectors' null data)
+    if (ids1 && !U.empty()) std::memcpy(ids1, U.data(), sizeof(int32_t) * U.size());
+    if (w1 && !A.empty()) std::memcpy(w1, A.data(), sizeof(float) * A.size());
     if (num_hops == 2) {
-        if (ids2) std::memcpy(ids2, W.data(), sizeof(int32_t) * W.size());
-        if (w2) std::memcpy(w2, Wt.data(), sizeof(float) * Wt.size());
+        if (ids2 && !W.empty()) std::memcpy(ids2, W.data(), sizeof(int32_t) * W.size());
+        if (w2 && !Wt.empty()) std::memcpy(w2, Wt.data(), sizeof(float) * Wt.size());
     }
     return orc_wmean_replay_fwd(x, x_dtype, D, num_nodes, U.data(), num_hops == 2 ? W.data() : nullptr,
                                 A.data(), num_hops == 2 ? Wt.data() : nullptr, B, k1, k2, out, out_h1);

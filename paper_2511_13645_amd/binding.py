@@ -109,8 +109,20 @@ def _need(t: torch.Tensor, name: str, dtype=None) -> None:
         raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
 
 
-def _stream(stream: Optional[torch.cuda.Stream]) -> int:
-    s = torch.cuda.current_stream() if stream is None else stream
+def _shape(t: Optional[torch.Tensor], name: str, shape) -> None:
+    if t is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must be %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+
+
+def _same_device(ref: torch.Tensor, *named) -> None:
+    for t, name in named:
+        if t is not None and t.device != ref.device:
+            raise ValueError("%s lives on %s, expected %s" % (name, t.device, ref.device))
+
+
+def _stream(stream: Optional[torch.cuda.Stream], like: torch.Tensor) -> int:
+    """The stream to launch on: the caller's, else the current stream of the device that holds `like`."""
+    s = torch.cuda.current_stream(like.device) if stream is None else stream
     return s.cuda_stream
 
 
@@ -141,14 +153,18 @@ def fsa_sample_mean_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.Te
         out_ids1 = torch.empty((B, k1), dtype=torch.int32, device=dev)
     if emit_ids and hops == 2 and out_ids2 is None:
         out_ids2 = torch.empty((B, k1, k2), dtype=torch.int32, device=dev)
-    for t, n in ((out, "out"), (out_h1, "out_h1"), (out_ids1, "out_ids1"), (out_ids2, "out_ids2")):
+    for t, n, dt, shp in ((out, "out", x.dtype, (B, D)), (out_h1, "out_h1", x.dtype, (B, k1, D)),
+                          (out_ids1, "out_ids1", torch.int32, (B, k1)), (out_ids2, "out_ids2", torch.int32, (B, k1, k2))):
         if t is not None:
-            _need(t, n)
+            _need(t, n, dt)
+            _shape(t, n, shp)
+    _same_device(x, (indptr, "indptr"), (indices, "indices"), (seeds, "seeds"), (out, "out"), (out_h1, "out_h1"),
+                 (out_ids1, "out_ids1"), (out_ids2, "out_ids2"))
     fan_host = (ctypes.c_int32 * max(1, hops))(*fan)
     rc = lib().fsa_sample_mean_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N,
                                    _ptr(x), _x_dtype(x), D, _ptr(seeds), B,
                                    ctypes.cast(fan_host, ctypes.c_void_p), hops, seed & (2**64 - 1),
-                                   _ptr(out), _ptr(out_h1), _ptr(out_ids1), _ptr(out_ids2), _stream(stream))
+                                   _ptr(out), _ptr(out_h1), _ptr(out_ids1), _ptr(out_ids2), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_sample_mean_fwd")
     return out, out_h1, out_ids1, out_ids2
@@ -172,8 +188,13 @@ def fsa_mean_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torc
         out = torch.empty((B, D), dtype=x.dtype, device=x.device)
     if ids2 is not None and emit_h1 and out_h1 is None:
         out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=x.device)
+    for t, n, shp in ((out, "out", (B, D)), (out_h1, "out_h1", (B, k1, D))):
+        if t is not None:
+            _need(t, n, x.dtype)
+            _shape(t, n, shp)
+    _same_device(x, (ids1, "ids1"), (ids2, "ids2"), (out, "out"), (out_h1, "out_h1"))
     rc = lib().fsa_mean_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), B, k1, k2,
-                                   _ptr(out), _ptr(out_h1), _stream(stream))
+                                   _ptr(out), _ptr(out_h1), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_replay_fwd")
     return out, out_h1
@@ -193,13 +214,15 @@ def fsa_mean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torc
     k2 = 0
     if ids2 is not None:
         _need(ids2, "ids2", torch.int32)
+        if ids2.dim() != 3 or tuple(ids2.shape[:2]) != (B, k1):
+            raise ValueError("ids2 must be [B,k1,k2]")
         k2 = ids2.shape[2]
     if grad_h1 is not None:
         _need(grad_h1, "grad_h1", torch.float32)
-        if tuple(grad_h1.shape) != (B, k1, D):
-            raise ValueError("grad_h1 must be [B,k1,D]")
+        _shape(grad_h1, "grad_h1", (B, k1, D))
+    _same_device(grad_x, (grad_out, "grad_out"), (grad_h1, "grad_h1"), (ids1, "ids1"), (ids2, "ids2"))
     rc = lib().fsa_mean_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(ids1), _ptr(ids2), B, k1, k2, D,
-                            _ptr(grad_x), N, _stream(stream))
+                            _ptr(grad_x), N, _stream(stream, grad_x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd")
     return grad_x
@@ -219,13 +242,15 @@ def fsa_mean_bwd_lp(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[t
     k2 = 0
     if ids2 is not None:
         _need(ids2, "ids2", torch.int32)
+        if ids2.dim() != 3 or tuple(ids2.shape[:2]) != (B, k1):
+            raise ValueError("ids2 must be [B,k1,k2]")
         k2 = ids2.shape[2]
     if grad_h1 is not None:
         _need(grad_h1, "grad_h1", grad_out.dtype)
-        if tuple(grad_h1.shape) != (B, k1, D):
-            raise ValueError("grad_h1 must be [B,k1,D]")
+        _shape(grad_h1, "grad_h1", (B, k1, D))
+    _same_device(grad_x, (grad_out, "grad_out"), (grad_h1, "grad_h1"), (ids1, "ids1"), (ids2, "ids2"))
     rc = lib().fsa_mean_bwd_lp(_ptr(grad_out), _ptr(grad_h1), _x_dtype(grad_out), _ptr(ids1), _ptr(ids2),
-                               B, k1, k2, D, _ptr(grad_x), _x_dtype(grad_x), N, _stream(stream))
+                               B, k1, k2, D, _ptr(grad_x), _x_dtype(grad_x), N, _stream(stream, grad_x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd_lp")
     return grad_x
@@ -241,6 +266,9 @@ def fsa_sample_mean_layerwise_fwd(indptr: torch.Tensor, indices: torch.Tensor, x
         raise ValueError("two fanouts expected")
     k1, k2 = fan
     B, (N, D), dev = seeds.shape[0], x.shape, x.device
+    if indptr.shape[0] != N + 1:
+        raise ValueError("indptr must have num_nodes+1 entries")
+    _same_device(x, (indptr, "indptr"), (indices, "indices"), (seeds, "seeds"))
     out = torch.empty((B, D), dtype=x.dtype, device=dev)
     out_m1 = torch.empty((B, D), dtype=x.dtype, device=dev)
     out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=dev) if emit_h1 else None
@@ -249,7 +277,7 @@ def fsa_sample_mean_layerwise_fwd(indptr: torch.Tensor, indices: torch.Tensor, x
     fan_host = (ctypes.c_int32 * 2)(*fan)
     rc = lib().fsa_sample_mean_layerwise_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N, _ptr(x), _x_dtype(x), D,
                                              _ptr(seeds), B, ctypes.cast(fan_host, ctypes.c_void_p), int(seed) & (2**64 - 1),
-                                             _ptr(out), _ptr(out_h1), _ptr(out_m1), _ptr(ids1), _ptr(ids2), _stream(stream))
+                                             _ptr(out), _ptr(out_h1), _ptr(out_m1), _ptr(ids1), _ptr(ids2), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_sample_mean_layerwise_fwd")
     return out, out_h1, out_m1, ids1, ids2
@@ -265,6 +293,9 @@ def fsa_sample_mean3_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.T
         raise ValueError("three fanouts expected")
     k1, k2, k3 = fan
     B, (N, D), dev = seeds.shape[0], x.shape, x.device
+    if indptr.shape[0] != N + 1:
+        raise ValueError("indptr must have num_nodes+1 entries")
+    _same_device(x, (indptr, "indptr"), (indices, "indices"), (seeds, "seeds"))
     r = {"out": torch.empty((B, D), dtype=x.dtype, device=dev),
          "out_h1": torch.empty((B, k1, D), dtype=x.dtype, device=dev),
          "out_h2": torch.empty((B, k1, k2, D), dtype=x.dtype, device=dev) if emit_h2 else None,
@@ -277,7 +308,7 @@ def fsa_sample_mean3_fwd(indptr: torch.Tensor, indices: torch.Tensor, x: torch.T
     rc = lib().fsa_sample_mean3_fwd(_ptr(indptr), _indptr_type(indptr), _ptr(indices), N, _ptr(x), _x_dtype(x), D,
                                     _ptr(seeds), B, ctypes.cast(fan_host, ctypes.c_void_p), int(seed) & (2**64 - 1),
                                     _ptr(r["out"]), _ptr(r["out_h1"]), _ptr(r["out_h2"]), _ptr(r["out_m1"]),
-                                    _ptr(r["ids1"]), _ptr(r["ids2"]), _ptr(r["ids3"]), _ptr(r["cnt2"]), _stream(stream))
+                                    _ptr(r["ids1"]), _ptr(r["ids2"]), _ptr(r["ids3"]), _ptr(r["cnt2"]), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_sample_mean3_fwd")
     return r
@@ -292,6 +323,7 @@ def fsa_mean3_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
         raise ValueError("ids1 / ids2 / ids3 shapes do not nest")
     N, D = x.shape
     dev = x.device
+    _same_device(x, (ids1, "ids1"), (ids2, "ids2"), (ids3, "ids3"))
     r = {"out": torch.empty((B, D), dtype=x.dtype, device=dev),
          "out_h1": torch.empty((B, k1, D), dtype=x.dtype, device=dev),
          "out_h2": torch.empty((B, k1, k2, D), dtype=x.dtype, device=dev) if emit_h2 else None,
@@ -299,7 +331,7 @@ def fsa_mean3_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
          "cnt2": torch.empty((B, k1), dtype=torch.int32, device=dev)}
     rc = lib().fsa_mean3_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), _ptr(ids3), B, k1, k2, k3,
                                     _ptr(r["out"]), _ptr(r["out_h1"]), _ptr(r["out_h2"]), _ptr(r["out_m1"]),
-                                    _ptr(r["cnt2"]), _stream(stream))
+                                    _ptr(r["cnt2"]), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean3_replay_fwd")
     return r
@@ -314,6 +346,12 @@ def fsa_mean3_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
     _need(ids1, "ids1", torch.int32); _need(ids2, "ids2", torch.int32); _need(ids3, "ids3", torch.int32)
     B, k1, k2, k3 = ids3.shape
     D = grad_out.shape[1]
+    _shape(ids1, "ids1", (B, k1)); _shape(ids2, "ids2", (B, k1, k2))
+    _shape(grad_out, "grad_out", (B, D))
+    if grad_x.dim() != 2 or grad_x.shape[1] != D:
+        raise ValueError("grad_x must be [N,%d]" % D)
+    _same_device(grad_x, (grad_out, "grad_out"), (grad_h1, "grad_h1"), (grad_h2, "grad_h2"), (grad_m1, "grad_m1"),
+                 (ids1, "ids1"), (ids2, "ids2"), (ids3, "ids3"), (work, "work"))
     for g, name, shape in ((grad_h1, "grad_h1", (B, k1, D)), (grad_h2, "grad_h2", (B, k1, k2, D)), (grad_m1, "grad_m1", (B, D))):
         if g is not None:
             _need(g, name, torch.float32)
@@ -321,10 +359,10 @@ def fsa_mean3_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
                 raise ValueError("%s must be %s" % (name, shape))
     if work is None:
         work = torch.empty((B, k1, D), dtype=torch.float32, device=grad_x.device)
-    elif work.numel() < B * k1 * D or work.dtype != torch.float32:
-        raise ValueError("work must hold B*k1*D floats")
+    elif work.numel() < B * k1 * D or work.dtype != torch.float32 or not work.is_cuda or not work.is_contiguous():
+        raise ValueError("work must be a contiguous GPU tensor that holds B*k1*D floats")
     rc = lib().fsa_mean3_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(grad_h2), _ptr(grad_m1), _ptr(ids1), _ptr(ids2), _ptr(ids3),
-                             B, k1, k2, k3, D, _ptr(grad_x), grad_x.shape[0], _ptr(work), _stream(stream))
+                             B, k1, k2, k3, D, _ptr(grad_x), grad_x.shape[0], _ptr(work), _stream(stream, grad_x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean3_bwd")
     return grad_x
@@ -344,6 +382,9 @@ def fsa_sample_wmean_fwd(indptr: torch.Tensor, indices: torch.Tensor, edge_weigh
     hops = len(fan)
     B, (N, D) = seeds.shape[0], x.shape
     dev = x.device
+    if indptr.shape[0] != N + 1:
+        raise ValueError("indptr must have num_nodes+1 entries")
+    _same_device(x, (indptr, "indptr"), (indices, "indices"), (edge_weight, "edge_weight"), (seeds, "seeds"))
     k1 = fan[0] if hops >= 1 else 0
     k2 = fan[1] if hops >= 2 else 0
     out = torch.empty((B, D), dtype=x.dtype, device=dev)
@@ -357,7 +398,7 @@ def fsa_sample_wmean_fwd(indptr: torch.Tensor, indices: torch.Tensor, edge_weigh
                                     _ptr(x), _x_dtype(x), D, _ptr(seeds), B,
                                     ctypes.cast(fan_host, ctypes.c_void_p), hops, seed & (2**64 - 1),
                                     _ptr(out), _ptr(out_h1), _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
-                                    _stream(stream))
+                                    _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_sample_wmean_fwd")
     return out, out_h1, ids1, ids2, w1, w2
@@ -370,14 +411,21 @@ def fsa_wmean_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, w1: torch.Tensor,
     _need(x, "x"); _need(ids1, "ids1", torch.int32); _need(w1, "w1", torch.float32)
     B, k1 = ids1.shape
     N, D = x.shape
+    _shape(w1, "w1", (B, k1))
     k2 = 0
     if ids2 is not None:
+        if w2 is None:
+            raise ValueError("ids2 needs w2")
         _need(ids2, "ids2", torch.int32); _need(w2, "w2", torch.float32)
+        if ids2.dim() != 3 or tuple(ids2.shape[:2]) != (B, k1):
+            raise ValueError("ids2 must be [B,k1,k2]")
         k2 = ids2.shape[2]
+        _shape(w2, "w2", (B, k1, k2))
+    _same_device(x, (ids1, "ids1"), (w1, "w1"), (ids2, "ids2"), (w2, "w2"))
     out = torch.empty((B, D), dtype=x.dtype, device=x.device)
     out_h1 = torch.empty((B, k1, D), dtype=x.dtype, device=x.device) if (ids2 is not None and emit_h1) else None
     rc = lib().fsa_wmean_replay_fwd(_ptr(x), _x_dtype(x), D, N, _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
-                                    B, k1, k2, _ptr(out), _ptr(out_h1), _stream(stream))
+                                    B, k1, k2, _ptr(out), _ptr(out_h1), _stream(stream, x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_wmean_replay_fwd")
     return out, out_h1
@@ -392,14 +440,24 @@ def fsa_wmean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, w1: torch.Tensor,
     _need(grad_x, "grad_x", torch.float32)
     B, k1 = ids1.shape
     D = grad_out.shape[1]
+    _shape(grad_out, "grad_out", (B, D)); _shape(w1, "w1", (B, k1))
+    if grad_x.dim() != 2 or grad_x.shape[1] != D:
+        raise ValueError("grad_x must be [N,%d]" % D)
     k2 = 0
     if ids2 is not None:
+        if w2 is None:
+            raise ValueError("ids2 needs w2")
         _need(ids2, "ids2", torch.int32); _need(w2, "w2", torch.float32)
+        if ids2.dim() != 3 or tuple(ids2.shape[:2]) != (B, k1):
+            raise ValueError("ids2 must be [B,k1,k2]")
         k2 = ids2.shape[2]
+        _shape(w2, "w2", (B, k1, k2))
     if grad_h1 is not None:
         _need(grad_h1, "grad_h1", torch.float32)
+        _shape(grad_h1, "grad_h1", (B, k1, D))
+    _same_device(grad_x, (grad_out, "grad_out"), (grad_h1, "grad_h1"), (ids1, "ids1"), (ids2, "ids2"), (w1, "w1"), (w2, "w2"))
     rc = lib().fsa_wmean_bwd(_ptr(grad_out), _ptr(grad_h1), _ptr(ids1), _ptr(ids2), _ptr(w1), _ptr(w2),
-                             B, k1, k2, D, _ptr(grad_x), grad_x.shape[0], _stream(stream))
+                             B, k1, k2, D, _ptr(grad_x), grad_x.shape[0], _stream(stream, grad_x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_wmean_bwd")
     return grad_x

@@ -54,20 +54,6 @@ def build_hip(extra_flags=(), verbose: bool = False) -> str:
     return LIB
 
 
-CEILINGS_LIB = os.path.join(HERE, "libfsa_ceilings.so")
-
-
-def build_ceilings(verbose: bool = False) -> str:
-    """The bandwidth / atomic-rate microbenchmarks that bench.py --ceilings runs (a library of its own)."""
-    tmp = CEILINGS_LIB + ".tmp.%d" % os.getpid()
-    cmd = [hipcc(), *HIPCC_FLAGS, "-shared", "-o", tmp, os.path.join(CSRC, "fsa_ceilings.hip")]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, cwd=CSRC)
-    os.replace(tmp, CEILINGS_LIB)
-    return CEILINGS_LIB
-
-
 def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -77,4 +63,3 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     print(build_hip(sys.argv[1:], verbose=True))
-    print(build_ceilings(verbose=True))

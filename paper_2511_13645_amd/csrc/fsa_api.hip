@@ -41,6 +41,13 @@ int check_common(int x_dtype, int64_t D, int64_t num_nodes, int64_t B) {
 
 int elem_bytes(int dtype) { return dtype == FSA_F32 ? 4 : 2; }
 
+// An error that an earlier HIP call of the caller left pending must not be reported as ours.
+void drop_stale_hip_error() { (void)hipGetLastError(); }
+
+// hipErrorInvalidValue comes from the launch code's own checks (fanouts that need more LDS than
+// the device has); anything else is the runtime refusing a launch.
+int status_of(hipError_t e) { return e == hipSuccess ? FSA_OK : e == hipErrorInvalidValue ? FSA_ERR_ARG : FSA_ERR_HIP; }
+
 bool fanout_ok(int32_t k) { return k >= 1 && k <= FSA_KMAX; }
 
 }  // namespace
@@ -67,6 +74,7 @@ int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indi
         !aligned(out_ids1, 4) || !aligned(out_ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
@@ -76,7 +84,7 @@ int fsa_sample_mean_fwd(const void* indptr, int indptr_type, const int32_t* indi
     a.ids1 = nullptr; a.ids2 = nullptr;
     a.out = out; a.out_h1 = out_h1; a.out_ids1 = out_ids1; a.out_ids2 = out_ids2;
     a.geom = row_geometry(D, eb, rows, 3);
-    return fsa::launch_forward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_forward(a, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
@@ -92,6 +100,7 @@ int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes
     if (!aligned(x, eb) || !aligned(out, eb) || !aligned(out_h1, eb) || !aligned(ids1, 4) || !aligned(ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
@@ -101,7 +110,7 @@ int fsa_mean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes
     a.ids1 = ids1; a.ids2 = ids2;
     a.out = out; a.out_h1 = out_h1; a.out_ids1 = nullptr; a.out_ids2 = nullptr;
     a.geom = row_geometry(D, eb, rows, 3);
-    return fsa::launch_forward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_forward(a, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
@@ -116,11 +125,12 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
     if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     fsa::BwdArgs a{};
     a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
     a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
-    return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_backward(a, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
@@ -142,12 +152,13 @@ int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
         !aligned(ids2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     fsa::BwdArgs a{};
     a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
     a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
     a.grad_kind = grad_dtype; a.grad_x_kind = grad_x_dtype;
-    return fsa::launch_backward(a, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_backward(a, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* indices,
@@ -172,6 +183,7 @@ int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
         !aligned(out_ids1, 4) || !aligned(out_ids2, 4) || !aligned(out_w1, 4) || !aligned(out_w2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
@@ -182,7 +194,7 @@ int fsa_sample_wmean_fwd(const void* indptr, int indptr_type, const int32_t* ind
     a.geom = row_geometry(D, eb, rows, 3);
     fsa::WeightArgs w{};
     w.edge_w = edge_weight; w.out_w1 = out_w1; w.out_w2 = out_w2;
-    return fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
@@ -200,6 +212,7 @@ int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
         !aligned(w1, 4) || !aligned(w2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     const void* rows[3] = {x, out, out_h1};
     fsa::FwdArgs a{};
@@ -209,7 +222,7 @@ int fsa_wmean_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
     a.geom = row_geometry(D, eb, rows, 3);
     fsa::WeightArgs w{};
     w.w1 = w1; w.w2 = w2;
-    return fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_forward_weighted(a, w, static_cast<hipStream_t>(stream)));
 }
 
 int fsa_wmean_bwd(const float* grad_out, const float* grad_h1,
@@ -226,13 +239,14 @@ int fsa_wmean_bwd(const float* grad_out, const float* grad_h1,
         !aligned(w1, 4) || !aligned(w2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
 
     fsa::BwdArgs a{};
     a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
     a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
     fsa::WeightArgs w{};
     w.w1 = w1; w.w2 = w2;
-    return fsa::launch_backward_weighted(a, w, static_cast<hipStream_t>(stream)) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(fsa::launch_backward_weighted(a, w, static_cast<hipStream_t>(stream)));
 }
 
 // ---- layer-wise and three-hop variants: chains of the kernels above on one stream ----------
@@ -288,6 +302,7 @@ int fsa_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* ind
         !aligned(out_ids1, 4) || !aligned(out_ids2, 4) || !aligned(out_ids3, 4) || !aligned(out_cnt2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     // hop 0: the seeds' rows -> ids1 and the plain hop-1 mean
@@ -298,7 +313,7 @@ int fsa_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* ind
         a.x = x; a.x_kind = x_dtype; a.D = D; a.seeds = seeds; a.B = B; a.k1 = k1; a.hops = 1; a.seed = seed;
         a.out = out_m1; a.out_ids1 = out_ids1;
         a.geom = row_geometry(D, eb, rows, 2);
-        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+        if (hipError_t e = fsa::launch_forward(a, st)) return status_of(e);
     }
     // hops 1 and 2: the fused two-hop kernel with the B*k1 hop-1 slots as its roots
     {
@@ -309,9 +324,9 @@ int fsa_sample_mean3_fwd(const void* indptr, int indptr_type, const int32_t* ind
         a.seed = seed; a.hop_base = 1;
         a.out = out_h1; a.out_h1 = out_h2; a.out_ids1 = out_ids2; a.out_ids2 = out_ids3; a.out_live = out_cnt2;
         a.geom = row_geometry(D, eb, rows, 3);
-        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+        if (hipError_t e = fsa::launch_forward(a, st)) return status_of(e);
     }
-    return slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st));
 }
 
 int fsa_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_nodes,
@@ -329,13 +344,14 @@ int fsa_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
         !aligned(ids1, 4) || !aligned(ids2, 4) || !aligned(ids3, 4) || !aligned(out_cnt2, 4))
         return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (out_m1) {
         const void* rows[2] = {x, out_m1};
         fsa::FwdArgs a{};
         a.x = x; a.x_kind = x_dtype; a.D = D; a.B = B; a.k1 = k1; a.hops = 1; a.ids1 = ids1; a.out = out_m1;
         a.geom = row_geometry(D, eb, rows, 2);
-        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+        if (hipError_t e = fsa::launch_forward(a, st)) return status_of(e);
     }
     {
         const void* rows[3] = {x, out_h1, out_h2};
@@ -344,41 +360,63 @@ int fsa_mean3_replay_fwd(const void* x, int x_dtype, int64_t D, int64_t num_node
         a.B = B * k1; a.k1 = k2; a.k2 = k3; a.hops = 2; a.ids1 = ids2; a.ids2 = ids3;
         a.out = out_h1; a.out_h1 = out_h2; a.out_live = out_cnt2;
         a.geom = row_geometry(D, eb, rows, 3);
-        if (fsa::launch_forward(a, st) != hipSuccess) return FSA_ERR_HIP;
+        if (hipError_t e = fsa::launch_forward(a, st)) return status_of(e);
     }
-    return slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st) == hipSuccess ? FSA_OK : FSA_ERR_HIP;
+    return status_of(slot_mean(out_h1, out_cnt2, x_dtype, D, B, k1, out, st));
 }
+
+namespace {
+
+int mean3_bwd_checked(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                      const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                      int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                      float* grad_x, int64_t num_nodes) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1 || !ids2 || !ids3)) return FSA_ERR_NULL;
+    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || !fanout_ok(k2) || !fanout_ok(k3)) return FSA_ERR_ARG;
+    if (B * k1 > (int64_t)INT32_MAX) return FSA_ERR_ARG;
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_h2, 4) || !aligned(grad_m1, 4) ||
+        !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4) || !aligned(ids3, 4))
+        return FSA_ERR_ALIGN;
+    return FSA_OK;
+}
+
+// The three launches of the three-hop backward; `work` holds B*k1*D floats.
+int mean3_bwd_launch(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                     const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                     int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                     float* grad_x, float* work, hipStream_t st) {
+    drop_stale_hip_error();
+    if (hipError_t e = fsa::launch_deep_grad(grad_out, grad_h1, ids1, ids2, ids3, work, B, k1, k2, k3, D, st)) return status_of(e);
+    {
+        fsa::BwdArgs a{};
+        a.grad_out = work; a.grad_h1 = grad_h2; a.ids1 = ids2; a.ids2 = ids3; a.root_valid = ids1;
+        a.B = B * k1; a.k1 = k2; a.k2 = k3; a.D = D; a.grad_x = grad_x;
+        if (hipError_t e = fsa::launch_backward(a, st)) return status_of(e);
+    }
+    if (grad_m1) {
+        fsa::BwdArgs a{};
+        a.grad_out = grad_m1; a.ids1 = ids1; a.B = B; a.k1 = k1; a.k2 = 0; a.D = D; a.grad_x = grad_x;
+        if (hipError_t e = fsa::launch_backward(a, st)) return status_of(e);
+    }
+    return FSA_OK;
+}
+
+}  // namespace
 
 int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
                   const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
                   int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
                   float* grad_x, int64_t num_nodes, float* work, void* stream) {
-    if (!grad_x) return FSA_ERR_NULL;
-    if (B != 0 && (!grad_out || !ids1 || !ids2 || !ids3 || !work)) return FSA_ERR_NULL;
-    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
-    if (!fanout_ok(k1) || !fanout_ok(k2) || !fanout_ok(k3)) return FSA_ERR_ARG;
-    if (B * k1 > (int64_t)INT32_MAX) return FSA_ERR_ARG;
-    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_h2, 4) || !aligned(grad_m1, 4) ||
-        !aligned(grad_x, 4) || !aligned(work, 4) || !aligned(ids1, 4) || !aligned(ids2, 4) || !aligned(ids3, 4))
-        return FSA_ERR_ALIGN;
+    if (B != 0 && !work) return FSA_ERR_NULL;
+    if (int rc = mean3_bwd_checked(grad_out, grad_h1, grad_h2, grad_m1, ids1, ids2, ids3, B, k1, k2, k3, D, grad_x, num_nodes))
+        return rc;
+    if (!aligned(work, 4)) return FSA_ERR_ALIGN;
     if (B == 0) return FSA_OK;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (fsa::launch_deep_grad(grad_out, grad_h1, ids1, ids2, ids3, work, B, k1, k2, k3, D, st) != hipSuccess)
-        return FSA_ERR_HIP;
-    {
-        fsa::BwdArgs a{};
-        a.grad_out = work; a.grad_h1 = grad_h2; a.ids1 = ids2; a.ids2 = ids3; a.root_valid = ids1;
-        a.B = B * k1; a.k1 = k2; a.k2 = k3; a.D = D; a.grad_x = grad_x;
-        if (fsa::launch_backward(a, st) != hipSuccess) return FSA_ERR_HIP;
-    }
-    if (grad_m1) {
-        fsa::BwdArgs a{};
-        a.grad_out = grad_m1; a.ids1 = ids1; a.B = B; a.k1 = k1; a.k2 = 0; a.D = D; a.grad_x = grad_x;
-        if (fsa::launch_backward(a, st) != hipSuccess) return FSA_ERR_HIP;
-    }
-    return FSA_OK;
+    return mean3_bwd_launch(grad_out, grad_h1, grad_h2, grad_m1, ids1, ids2, ids3, B, k1, k2, k3, D, grad_x, work,
+                            static_cast<hipStream_t>(stream));
 }
-
 
 #ifdef FSA_TRACE
 // Debug builds only: device buffer [B][4] of int64 that the 2-hop forward stamps (NULL = off).

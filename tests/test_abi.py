@@ -162,13 +162,14 @@ def test_layerwise_and_three_hop_entry_points_reject_bad_arguments(fsa):
     assert b3(k2=0) == -2 and b3(D=0) == -2 and b3(w=FAKE + 2) == -4 and b3(B=0) == 0 and b3(B=0, w=None) == 0
 
 
+
 def test_ceilings_library_builds_and_exports_its_entry_point():
     """The measurement aid of bench.py --ceilings: its own library, one entry point, bad arguments refused
     before anything touches a GPU."""
-    from paper_2511_13645_amd import build
-    if not os.path.exists(build.CEILINGS_LIB):
-        build.build_ceilings()
-    C = ctypes.CDLL(build.CEILINGS_LIB)
+    import bench
+    if not os.path.exists(bench.CEILINGS_LIB):
+        bench.build_ceilings()
+    C = ctypes.CDLL(bench.CEILINGS_LIB)
     C.fsa_ceilings_measure.argtypes = [ctypes.c_int, ctypes.c_void_p]
     C.fsa_ceilings_measure.restype = ctypes.c_int
     out = (ctypes.c_double * 7)()

@@ -161,3 +161,37 @@ def test_weighted_backward_with_heavily_shared_rows(fsa, orc, n_targets, B):
     x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
     seeds = np.concatenate([np.arange(0, n, 97)[:50], rng.integers(0, n, B - 50)]).astype(np.int32)
     _run(fsa, orc, indptr, indices, ew, x, seeds, [k], 3, "weighted shared rows %d" % n_targets)
+
+
+def test_weighted_maximum_fanouts_with_one_wave_per_root(fsa, orc):
+    """Fanouts 64/64 at a batch size that gives every root a single wave: the weighted strips
+    (row offsets, weights, records for 4096 leaf slots) are the most LDS any launch asks for.
+    The launch code sizes them against the device limit (more waves per root if one strip does
+    not fit); the oracle checks the first 48 seeds, the backward runs over the whole batch."""
+    n, D, B, fan = 3000, 32, 4100, [64, 64]
+    indptr, indices, ew = _graph(n, seed=5, max_deg=200)
+    rng = np.random.default_rng(0)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
+    seeds = rng.integers(0, n, B).astype(np.int32)
+    dev = "cuda:0"
+    r_out, r_h1, r_ids1, r_ids2, r_w1, r_w2 = orc.sample_wmean_fwd(indptr, indices, ew, x.numpy(), seeds[:48], fan, 3)
+    d_x = x.to(dev)
+    out, h1, ids1, ids2, w1, w2 = fsa.fsa_sample_wmean_fwd(torch.from_numpy(indptr).to(dev), torch.from_numpy(indices).to(dev),
+                                                           torch.from_numpy(ew).to(dev), d_x, torch.from_numpy(seeds).to(dev), fan, 3)
+    torch.cuda.synchronize()
+    assert_ids_equal(ids1[:48], r_ids1, "ids1")
+    assert_ids_equal(ids2[:48], r_ids2, "ids2")
+    assert np.array_equal(w1[:48].cpu().numpy(), r_w1) and np.array_equal(w2[:48].cpu().numpy(), r_w2)
+    a_out, a_h1 = _scales(d_x, ids1[:48], ids2[:48], w1[:48], w2[:48])
+    assert_close(to_f64(out[:48]), r_out, a_out, 1e-5, "out")
+    assert_close(to_f64(h1[:48]), r_h1, a_h1, 1e-5, "out_h1")
+    rp_out, rp_h1 = fsa.fsa_wmean_replay_fwd(d_x, ids1, w1, ids2, w2)
+    torch.cuda.synchronize()
+    assert torch.equal(rp_out, out) and torch.equal(rp_h1, h1)
+    g = torch.from_numpy(rng.standard_normal((B, D)).astype(np.float32)).to(dev)
+    gx = fsa.fsa_wmean_bwd(g, ids1, w1, ids2, w2, grad_x=torch.zeros((n, D), device=dev))
+    torch.cuda.synchronize()
+    a = (ids1.cpu().numpy(), w1.cpu().numpy(), ids2.cpu().numpy(), w2.cpu().numpy())
+    want = orc.wmean_bwd(to_f64(g), *a, None, num_nodes=n)
+    mag = orc.wmean_bwd(np.abs(to_f64(g)), *a, None, num_nodes=n)
+    assert_close(to_f64(gx), want, mag, 1e-5, "grad_x")
