@@ -42,7 +42,8 @@
  *     launches, so FSA_ERR_HIP always refers to this call.  FSA_ERR_ARG is also returned when
  *     the fanouts need more LDS than the device offers.
  *     B == 0 returns FSA_OK without a launch (batch-sized arrays may then be NULL).
- *   - The library reads no environment variable and keeps no state between calls.
+ *   - The library reads no environment variable and keeps no state between calls (one
+ *     exception, stated there: fsa_mean3_bwd_noalloc remembers a device address).
  *   - grad_x (backward entry points) must be ordinary coarse-grained device memory
  *     (hipMalloc; not fine-grained, host-mapped or managed memory): the kernels add into it
  *     with hardware floating-point atomics resolved in the device's L2, which other kinds of
@@ -71,7 +72,8 @@ typedef enum {
     FSA_ERR_ARG = -2,     /* a size, fanout or hop count is out of range                  */
     FSA_ERR_DTYPE = -3,   /* unknown fsa_dtype / fsa_itype                                */
     FSA_ERR_ALIGN = -4,   /* a pointer is not aligned to its element size                 */
-    FSA_ERR_HIP = -5      /* the HIP runtime refused the launch                           */
+    FSA_ERR_HIP = -5,     /* the HIP runtime refused the launch                           */
+    FSA_ERR_SCRATCH = -6  /* the call needs more scratch than the library's fixed array   */
 } fsa_status;
 
 enum { FSA_KMAX = 64 };   /* largest fanout per hop (one wavefront lane per Floyd step)   */
@@ -219,6 +221,24 @@ int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad
                   int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
                   float* grad_x, int64_t num_nodes, float* work, void* stream);
 
+/*
+ * fsa_mean3_bwd for callers that cannot allocate device memory or hand over a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same
+ * kernels and the same result as fsa_mean3_bwd; the scratch array (the gradient of each hop-1
+ * slot, B*k1*D floats) lives in a fixed device array inside the library instead of `work`.
+ *   - Limit: B*k1*D <= FSA_SCRATCH_FLOATS (32 MiB of floats), else FSA_ERR_SCRATCH and nothing
+ *     is launched.  Every GPU the library runs on holds that array until the process ends.
+ *   - The call allocates nothing and frees nothing.  Its first call on a device looks up the
+ *     array's address on that device (with that device current) and keeps it for later calls.
+ *   - All calls on one GPU share the array: calls that overlap on one GPU (different streams,
+ *     or threads) race on it and must be serialised by the caller.  Every element a call reads
+ *     is written by the same call first, so nothing needs clearing between calls.
+ */
+enum { FSA_SCRATCH_FLOATS = 8 * 1024 * 1024 };
+int fsa_mean3_bwd_noalloc(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                          const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                          int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                          float* grad_x, int64_t num_nodes, void* stream);
 
 /*
  * Weighted mean (Sec. 3.2, "Extension Feasibility": the same fusion with weighted numerators

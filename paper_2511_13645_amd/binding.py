@@ -20,9 +20,11 @@ FSA_F32, FSA_BF16, FSA_F16 = 0, 1, 2
 FSA_I32, FSA_I64 = 0, 1
 FSA_OK = 0
 FSA_KMAX = 64
+FSA_SCRATCH_FLOATS = 8 * 1024 * 1024
 
 EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_mean_bwd_lp", "fsa_status_string",
            "fsa_sample_mean_layerwise_fwd", "fsa_sample_mean3_fwd", "fsa_mean3_replay_fwd", "fsa_mean3_bwd",
+           "fsa_mean3_bwd_noalloc",
            "fsa_sample_wmean_fwd", "fsa_wmean_replay_fwd", "fsa_wmean_bwd")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -68,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.fsa_mean3_replay_fwd.restype = ci
         L.fsa_mean3_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, vp, i64, vp, vp]
         L.fsa_mean3_bwd.restype = ci
+        L.fsa_mean3_bwd_noalloc.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i32, i32, i32, i64, vp, i64, vp]
+        L.fsa_mean3_bwd_noalloc.restype = ci
         L.fsa_status_string.argtypes = [ci]
         L.fsa_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -340,8 +344,10 @@ def fsa_mean3_replay_fwd(x: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
 def fsa_mean3_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor, ids3: torch.Tensor, *,
                   grad_h1: Optional[torch.Tensor] = None, grad_h2: Optional[torch.Tensor] = None,
                   grad_m1: Optional[torch.Tensor] = None, grad_x: torch.Tensor,
-                  work: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
-    """Scatter-add the three-hop mean's gradient into grad_x [N,D] fp32 (accumulated, not zeroed)."""
+                  work: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None,
+                  noalloc: bool = False) -> torch.Tensor:
+    """Scatter-add the three-hop mean's gradient into grad_x [N,D] fp32 (accumulated, not zeroed).
+    noalloc=True calls fsa_mean3_bwd_noalloc: no workspace, the library's fixed scratch array."""
     _need(grad_out, "grad_out", torch.float32); _need(grad_x, "grad_x", torch.float32)
     _need(ids1, "ids1", torch.int32); _need(ids2, "ids2", torch.int32); _need(ids3, "ids3", torch.int32)
     B, k1, k2, k3 = ids3.shape
@@ -357,6 +363,12 @@ def fsa_mean3_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: torch.Tensor
             _need(g, name, torch.float32)
             if tuple(g.shape) != shape:
                 raise ValueError("%s must be %s" % (name, shape))
+    if noalloc:
+        rc = lib().fsa_mean3_bwd_noalloc(_ptr(grad_out), _ptr(grad_h1), _ptr(grad_h2), _ptr(grad_m1), _ptr(ids1), _ptr(ids2),
+                                         _ptr(ids3), B, k1, k2, k3, D, _ptr(grad_x), grad_x.shape[0], _stream(stream, grad_x))
+        if rc != FSA_OK:
+            raise FsaError(rc, "fsa_mean3_bwd_noalloc")
+        return grad_x
     if work is None:
         work = torch.empty((B, k1, D), dtype=torch.float32, device=grad_x.device)
     elif work.numel() < B * k1 * D or work.dtype != torch.float32 or not work.is_cuda or not work.is_contiguous():

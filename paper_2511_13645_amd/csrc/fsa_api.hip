@@ -1,11 +1,39 @@
 // The C ABI declared in include/fsa.h: host-side validation, row geometry, dispatch.
-// Nothing here allocates, synchronises or keeps state.
+// Nothing here allocates or synchronises; the only thing kept between calls is the device address
+// of the fixed scratch array of fsa_mean3_bwd_noalloc.
 #include "../../include/fsa.h"
 #include "fsa_internal.h"
+
+#include <atomic>
 
 #ifdef FSA_TRACE
 namespace fsa { long long* g_trace = nullptr; }
 #endif
+
+// Scratch of fsa_mean3_bwd_noalloc: one copy per GPU, at an address of its own on each.  In host
+// code the array's name is only a handle for hipGetSymbolAddress; kernels get the looked-up pointer.
+static __device__ __align__(256) float scratch[FSA_SCRATCH_FLOATS];
+
+static constexpr int kMaxDevices = 64;
+static std::atomic<float*> scratch_on_device[kMaxDevices];
+
+// Device address of `scratch` on the current device, looked up once per device.
+static float* scratch_pointer() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    float* p = scratch_on_device[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void* sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        p = static_cast<float*>(sym);
+        scratch_on_device[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
 
 namespace {
 
@@ -418,6 +446,21 @@ int fsa_mean3_bwd(const float* grad_out, const float* grad_h1, const float* grad
                             static_cast<hipStream_t>(stream));
 }
 
+int fsa_mean3_bwd_noalloc(const float* grad_out, const float* grad_h1, const float* grad_h2, const float* grad_m1,
+                          const int32_t* ids1, const int32_t* ids2, const int32_t* ids3,
+                          int64_t B, int32_t k1, int32_t k2, int32_t k3, int64_t D,
+                          float* grad_x, int64_t num_nodes, void* stream) {
+    if (int rc = mean3_bwd_checked(grad_out, grad_h1, grad_h2, grad_m1, ids1, ids2, ids3, B, k1, k2, k3, D, grad_x, num_nodes))
+        return rc;
+    if (B == 0) return FSA_OK;
+    if (B * k1 > (int64_t)FSA_SCRATCH_FLOATS / D) return FSA_ERR_SCRATCH;   // B*k1*D floats would not fit
+    float* work = scratch_pointer();
+    if (!work) return FSA_ERR_HIP;
+    return mean3_bwd_launch(grad_out, grad_h1, grad_h2, grad_m1, ids1, ids2, ids3, B, k1, k2, k3, D, grad_x, work,
+                            static_cast<hipStream_t>(stream));
+}
+
+
 #ifdef FSA_TRACE
 // Debug builds only: device buffer [B][4] of int64 that the 2-hop forward stamps (NULL = off).
 void fsa_debug_set_trace(void* device_buffer) { fsa::g_trace = static_cast<long long*>(device_buffer); }
@@ -431,6 +474,7 @@ const char* fsa_status_string(int status) {
         case FSA_ERR_DTYPE: return "unknown element type";
         case FSA_ERR_ALIGN: return "a pointer is not aligned to its element size";
         case FSA_ERR_HIP:   return "the HIP runtime refused the launch";
+        case FSA_ERR_SCRATCH: return "the call needs more scratch memory than the library's fixed array holds";
         default:            return "unknown status";
     }
 }

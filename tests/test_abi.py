@@ -161,6 +161,17 @@ def test_layerwise_and_three_hop_entry_points_reject_bad_arguments(fsa):
     assert b3(go=None) == -1 and b3(gx=None) == -1 and b3(w=None) == -1 and b3(i2=None) == -1
     assert b3(k2=0) == -2 and b3(D=0) == -2 and b3(w=FAKE + 2) == -4 and b3(B=0) == 0 and b3(B=0, w=None) == 0
 
+    # the variant without a workspace: the same checks, and sizes beyond its fixed scratch array are refused
+    def b3n(**k):
+        a = dict(go=FAKE, g1=FAKE, g2=FAKE, gm=FAKE, i1=FAKE, i2=FAKE, i3=FAKE, B=4, k1=3, k2=2, k3=2, D=8, gx=FAKE, n=10, s=None)
+        a.update(k)
+        return L.fsa_mean3_bwd_noalloc(*[a[n] for n in ("go", "g1", "g2", "gm", "i1", "i2", "i3", "B", "k1", "k2", "k3", "D", "gx", "n",
+                                                        "s")])
+    assert b3n(go=None) == -1 and b3n(gx=None) == -1 and b3n(i3=None) == -1 and b3n(k3=65) == -2 and b3n(gx=FAKE + 1) == -4
+    assert b3n(B=0) == 0
+    lim = fsa.FSA_SCRATCH_FLOATS
+    assert b3n(B=lim // (3 * 8) + 1) == -6 and b3n(B=1 << 20, k1=64, D=4096) == -6
+    assert "scratch" in fsa.status_string(-6)
 
 
 def test_ceilings_library_builds_and_exports_its_entry_point():
