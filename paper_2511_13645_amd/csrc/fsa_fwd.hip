@@ -49,6 +49,9 @@ struct FwdParams {
     int32_t* out_live;                      // 2-hop, nullable: [B] hop-1 slots that took part
     const int32_t* slot_cnt;                // slot-mean kernel only: [B,k1] counts, > 0 = takes part
     int waves_per_root;                     // 2-hop: waves that share one root (1: every wave has a root of its own)
+    uint32_t hop1;                          // 2-hop kernel: hop counter of the rows its (slot, step) lanes sample
+    int64_t packed_seeds;                   // > 0: the 2-hop kernel runs a 1-hop call over this many seeds, k1 of
+                                            // them per wave as its "slots" (see launch_typed); 0 otherwise
 #ifdef FSA_TRACE
     long long* trace;                       // debug builds: [B][4] start, gather start, end (10 ns units), leaf rows
 #endif
@@ -262,6 +265,10 @@ __global__ __launch_bounds__(256) void slot_mean_kernel(const FwdParams p) {
 // ---------------------------------------------------------------------------------------
 constexpr int kPassGroup = FSA_PASS_GROUP;
 constexpr int kRootsPerWorkgroup = FSA_ROOTS_PER_WG;             // with one wave per root
+#ifndef FSA_FWD1_PACKED_PASSES
+#define FSA_FWD1_PACKED_PASSES 4
+#endif
+constexpr int kFwd1PackedPasses = FSA_FWD1_PACKED_PASSES;        // sampling passes of a packed 1-hop wave
 
 // MT > 0 selects the gather for rows wider than one tile of 64 lanes (2 .. MT tiles, MT at
 // most kMultiTiles): all tiles of a row are loaded back to back, so the cache line that two
@@ -291,6 +298,11 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
     const int64_t b = nw == 1 ? (int64_t)blockIdx.x * n_strips + strip : (int64_t)blockIdx.x;
     if (b >= p.B) return;                                          // nw == 1 only; no block barrier on that path
     const int k1 = p.k1, k2 = p.k2;
+    // A packed 1-hop call: this wave's "hop-1 slots" are the seeds b*k1 .. b*k1+k1-1 themselves and
+    // its per-slot outputs are the call's outputs; the last wave may have fewer seeds than k1, and
+    // nothing may be read or written for the missing ones.
+    const int64_t seeds_left = p.packed_seeds > 0 ? p.packed_seeds - b * k1 : (int64_t)k1;
+    const int k1_live = seeds_left < (int64_t)k1 ? (int)seeds_left : k1;
     FSA_STAMP(t_start);
 
     const int nq_max = (k1 + nw - 1) / nw;
@@ -310,15 +322,24 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
     float* red = reinterpret_cast<float*>(live_slots + round_up4(n_strips));
 
     // hop 0, redundantly in every wave: lane j holds U[j]
-    float a_mine;
-    const int u_mine = hop0_id<REPLAY, WEIGHTED>(p, b, lane, draws, a_mine);
+    float a_mine = 0.0f;
+    int u_mine;
+    if (p.packed_seeds > 0) {                                      // kernel-uniform
+        u_mine = -1;
+        if (lane < k1_live) {
+            if constexpr (REPLAY) u_mine = 0;                      // any node: a replayed slot only needs to exist
+            else u_mine = p.seeds[b * k1 + lane];                  // (a negative seed is an empty row)
+        }
+    } else {
+        u_mine = hop0_id<REPLAY, WEIGHTED>(p, b, lane, draws, a_mine);
+    }
     if (!REPLAY && wave == 0 && lane < k1) {
         if (p.out_ids1) p.out_ids1[b * k1 + lane] = u_mine;
         if constexpr (WEIGHTED) { if (p.out_w1) p.out_w1[b * k1 + lane] = u_mine >= 0 ? a_mine : 0.0f; }
     }
 
     // owned slots: j = wave + q*nw, q < nq; lane q keeps slot q's node, row start, degree, count
-    const int nq = owned_slots(k1, nw, wave);
+    const int nq = owned_slots(k1_live, nw, wave);
     int u_own = u_mine;
     float a_own = a_mine;
     if (nw != 1) {
@@ -437,7 +458,7 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
                     const int64_t s = (int64_t)(((uint64_t)(uint32_t)rc.y << 32) | (uint32_t)rc.x);
                     const int64_t deg = (int64_t)(uint32_t)rc.z;
                     uint32_t wd = 0u;
-                    if (__any(active && deg > (int64_t)k2)) wd = floyd_word(p.seed, (uint32_t)u, p.hop_base + 1u, li);   // wave-uniform
+                    if (__any(active && deg > (int64_t)k2)) wd = floyd_word(p.seed, (uint32_t)u, p.hop1, li);   // wave-uniform
                     const int64_t pos = floyd_resolve(floyd_bound(wd, k2, li, deg), k2, li, seg_base, deg, active, lane,
                                                       draws);
                     if (pos >= 0) {
@@ -586,7 +607,7 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
                     }
 #pragma unroll
                     for (int e = 0; e < VE; ++e) root[t][e] *= inv1;
-                    if (live) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(root[t]);
+                    if (live && p.out) *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + (int64_t)chunk * VB) = C::pack(root[t]);
                 } else {
 #pragma unroll
                     for (int e = 0; e < VE; ++e) red[(wave * kWave + lane) * VE + e] = root[t][e];
@@ -726,7 +747,7 @@ __global__ __launch_bounds__(512) void fwd2_kernel(const FwdParams p) {
                     if (c0 == 0 && lane == 0 && p.out_live) p.out_live[b] = c1;
                     inv1 = inv_count(c1 > 0 ? c1 : 1);
                 }
-                if (sg == 0 && live) {
+                if (sg == 0 && live && p.out) {                        // (a packed 1-hop call has no root mean)
 #pragma unroll
                     for (int e = 0; e < VE; ++e) root[e] *= inv1;
                     *reinterpret_cast<Raw*>(p.out + b * p.row_bytes + chunk_off) = C::pack(root);
@@ -788,6 +809,24 @@ int fwd2_waves(int64_t B, int k1, const RowGeom&) {
     return nw;
 }
 
+// Seeds per wave of a 1-hop call, or 0 for a wave per seed.  A wave per seed gives every seed the
+// most lanes and loads in flight, which is best while the batch is within a few times the chip's
+// wave slots (256 CUs x 4 SIMDs x 8 waves = 8192); beyond that, packing several seeds into one
+// wave (64/k of them per sampling pass, at most kFwd1PackedPasses passes) multiplies the seeds in
+// flight, and the launch is fastest with about one wave per slot.  Measured on the KG shape
+// (2 rows per seed on average): B=65536 29.4 -> 23.7 us, B=262144 110 -> 68 us; at B=16384 a wave
+// per seed is still ahead (11.1 against 12.3 us).
+int fwd1_seeds_per_wave(int64_t B, int k) {
+    const int forced = tune_int("FSA_FWD1_SEEDS_PER_WAVE", -1);
+    if (forced >= 0) return forced > 64 ? 64 : forced;
+    const int spw = kWave / k;
+    if (B < 32768 || spw < 2) return 0;
+    int64_t K = B / 8192;
+    const int most = spw * kFwd1PackedPasses > 64 ? 64 : spw * kFwd1PackedPasses;
+    if (K > most) K = most;
+    return (int)K;                                                 // >= 4
+}
+
 // Dynamic LDS one workgroup may ask for on the current device.
 static size_t lds_limit() {
     int dev = 0, v = 0;
@@ -815,7 +854,39 @@ static hipError_t launch_typed(const FwdArgs& a, const FwdParams& p_in, hipStrea
             return hipGetLastError();
         }
     }
-    if (a.hops == 1) {
+    if (a.hops == 1 && fwd1_seeds_per_wave(a.B, a.k1) > 0 && !a.slot_cnt) {
+        // Large 1-hop batches: several seeds per wave through the 2-hop kernel.  A seed of a sparse
+        // graph names a handful of rows, so a wave of its own spends its life on the chain of
+        // dependent loads (seed -> indptr -> indices -> rows) for a kilobyte or two; once the batch
+        // exceeds the chip's wave slots that chain, not bandwidth, sets the rate.  Here a wave
+        // takes K seeds as the "hop-1 slots" of the 2-hop kernel (hop 0 is skipped: its IDs are
+        // the seeds), samples 64/k1 of them per pass with the seeds' own hop counter, and the
+        // per-slot outputs of that kernel (mean, IDs, weights) are this call's outputs.
+        const int K = fwd1_seeds_per_wave(a.B, a.k1);
+        const size_t lds = (size_t)fwd2_lds_bytes(K, a.k1, 1, 1, WEIGHTED, a.geom.sub, VE);
+        if (lds > lds_limit()) return hipErrorInvalidValue;
+        p.packed_seeds = a.B;
+        p.B = (a.B + K - 1) / K;
+        p.k1 = K; p.k2 = a.k1;
+        p.hop1 = a.hop_base;
+        p.out_h1 = p.out; p.out = nullptr;
+        p.out_ids2 = p.out_ids1; p.out_ids1 = nullptr;
+        p.out_w2 = p.out_w1; p.out_w1 = nullptr;
+        p.ids2 = p.ids1; p.ids1 = nullptr;
+        p.w2 = p.w1; p.w1 = nullptr;
+        p.out_live = nullptr;
+        p.waves_per_root = 1;
+        const dim3 grid((unsigned)p.B), block(kWave);
+#define FSA_LAUNCH_FWD1P(MT_)                                                                                            \
+        do {                                                                                                             \
+            if (replay) hipLaunchKernelGGL((fwd2_kernel<XT, VB, true, MT_, WEIGHTED>), grid, block, lds, stream, p);     \
+            else        hipLaunchKernelGGL((fwd2_kernel<XT, VB, false, MT_, WEIGHTED>), grid, block, lds, stream, p);    \
+        } while (0)
+        if (mt == 0) FSA_LAUNCH_FWD1P(0);
+        else if (mt == 4) FSA_LAUNCH_FWD1P(4);
+        else FSA_LAUNCH_FWD1P(8);
+#undef FSA_LAUNCH_FWD1P
+    } else if (a.hops == 1) {
         const int wpb_t = tune_int("FSA_FWD1_WAVES", 4);
         const int wpb = wpb_t >= 1 && wpb_t <= 4 ? wpb_t : 4;
         const dim3 grid((unsigned)((a.B + wpb - 1) / wpb)), block(wpb * kWave);
@@ -874,6 +945,8 @@ static hipError_t launch_forward_any(const FwdArgs& a, const WeightArgs* w, hipS
     p.sub_shift = __builtin_ctz((unsigned)a.geom.sub); p.indptr_is64 = a.indptr_is64;
     p.hop_base = a.hop_base; p.out_live = a.out_live; p.slot_cnt = a.slot_cnt;
     p.waves_per_root = 1;
+    p.hop1 = a.hop_base + 1u;
+    p.packed_seeds = 0;
 #ifdef FSA_TRACE
     p.trace = g_trace;
 #endif
