@@ -208,9 +208,25 @@ def measure_paths(L, binding, synth, torch, w, B, dev, n_launch=20, replay=True,
         b_alg = 2 * payload + 4 * leaf + B * D * 4 + (B * k1 * D * 4 if hops == 2 else 0)
         r["backward"] = block(b_ms, b_alg, atomic_payload_gbps=payload / (b_ms * 1e-3) / 1e9,
                               vs_forward=b_ms / f_ms)
+        # the same backward given a workspace: wide-row 2-hop shapes then update each destination
+        # row once, without atomics (other shapes take the atomic route again and are not repeated)
+        ws_bytes = int(L.fsa_mean_bwd_workspace_bytes(B, k1, k2, D)) if hops == 2 else 0
+        if ws_bytes > 0:
+            ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+            p_ws = ws.data_ptr()
+
+            def bwd_ws(i):
+                rc = L.fsa_mean_bwd_ws(p_go, p_gh, id1_p[i], i2(i), B, k1, k2, D, p_gx, N, p_ws, ws_bytes, stream)
+                if rc != 0:
+                    raise RuntimeError("fsa_mean_bwd_ws -> %d" % rc)
+            w_ms = timed(bwd_ws)
+            r["backward_with_workspace"] = block(w_ms, b_alg, payload_gbps=payload / (w_ms * 1e-3) / 1e9,
+                                                 vs_forward=w_ms / f_ms, workspace_bytes=ws_bytes)
+            del ws
         del g_out, g_h1, grad_x
     log("[bench] %s B=%d %s: %s" % (w.name, B, r["dtype"], ", ".join(
-        "%s %.1f us (%.3f)" % (k, r[k]["launch_us"], r[k]["frac"]) for k in ("forward", "replay_forward", "backward") if k in r)))
+        "%s %.1f us (%.3f)" % (k, r[k]["launch_us"], r[k]["frac"])
+        for k in ("forward", "replay_forward", "backward", "backward_with_workspace") if k in r)))
     return r
 
 

@@ -129,6 +129,29 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
                  float* grad_x, int64_t num_nodes, void* stream);
 
 /*
+ * fsa_mean_bwd with a caller workspace (same arguments, same result within the same tolerance).
+ * The atomic backward is bound by the L2 atomic unit (one 4-byte add per channel and clock), and
+ * that cost grows with the row width.  Given a workspace, 2-hop calls with wide rows
+ * (at least 1024 bytes, at most 8 x 64 chunks of 16 / 8 / 4 bytes -- the widest the row size and
+ * the pointers' alignment allow -- and at least 32 MiB of row updates per call) take another route: the
+ * leaf entries are binned by destination row, each bin is sorted in LDS, the gradients that reach
+ * one row are summed in registers and the row is updated once with plain loads and stores by the
+ * one workgroup that owns it (Sec. 3.3 only fixes WHICH rows receive gradient; how is ours).
+ * Without overflow of a bin (rows sampled thousands of times in one batch) that route is
+ * bit-reproducible.  Calls that are not eligible, a NULL workspace, one that is too small or not
+ * 256-byte aligned: the call behaves exactly as fsa_mean_bwd.
+ *   workspace        device memory, contents irrelevant on entry, overwritten
+ *   workspace_bytes  its size; fsa_mean_bwd_workspace_bytes(B,k1,k2,D) returns what the call can
+ *                    use (0: this shape always takes the atomic route)
+ */
+int64_t fsa_mean_bwd_workspace_bytes(int64_t B, int32_t k1, int32_t k2, int64_t D);
+int fsa_mean_bwd_ws(const float* grad_out, const float* grad_h1,
+                    const int32_t* ids1, const int32_t* ids2,
+                    int64_t B, int32_t k1, int32_t k2, int64_t D,
+                    float* grad_x, int64_t num_nodes,
+                    void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Reduced-precision backward (the paper lists FP32-only kernels as a limitation, Sec. 5
  * "Limitations"; this entry point lifts it).  Same operation as fsa_mean_bwd with
  *   grad_out / grad_h1 of type grad_dtype  (FSA_F32, FSA_BF16 or FSA_F16), and

@@ -24,7 +24,7 @@ FSA_SCRATCH_FLOATS = 8 * 1024 * 1024
 
 EXPORTS = ("fsa_sample_mean_fwd", "fsa_mean_replay_fwd", "fsa_mean_bwd", "fsa_mean_bwd_lp", "fsa_status_string",
            "fsa_sample_mean_layerwise_fwd", "fsa_sample_mean3_fwd", "fsa_mean3_replay_fwd", "fsa_mean3_bwd",
-           "fsa_mean3_bwd_noalloc",
+           "fsa_mean3_bwd_noalloc", "fsa_mean_bwd_ws", "fsa_mean_bwd_workspace_bytes",
            "fsa_sample_wmean_fwd", "fsa_wmean_replay_fwd", "fsa_wmean_bwd")
 
 _lib: Optional[ctypes.CDLL] = None
@@ -51,6 +51,10 @@ def lib() -> ctypes.CDLL:
         L.fsa_mean_replay_fwd.restype = ci
         L.fsa_mean_bwd.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp]
         L.fsa_mean_bwd.restype = ci
+        L.fsa_mean_bwd_ws.argtypes = [vp, vp, vp, vp, i64, i32, i32, i64, vp, i64, vp, i64, vp]
+        L.fsa_mean_bwd_ws.restype = ci
+        L.fsa_mean_bwd_workspace_bytes.argtypes = [i64, i32, i32, i64]
+        L.fsa_mean_bwd_workspace_bytes.restype = i64
         L.fsa_mean_bwd_lp.argtypes = [vp, vp, ci, vp, vp, i64, i32, i32, i64, vp, ci, i64, vp]
         L.fsa_mean_bwd_lp.restype = ci
         L.fsa_sample_wmean_fwd.argtypes = [vp, ci, vp, vp, i64, vp, ci, i64, vp, i64, vp, ci, u64,
@@ -229,6 +233,45 @@ def fsa_mean_bwd(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torc
                             _ptr(grad_x), N, _stream(stream, grad_x))
     if rc != FSA_OK:
         raise FsaError(rc, "fsa_mean_bwd")
+    return grad_x
+
+
+def fsa_mean_bwd_workspace_bytes(B: int, k1: int, k2: int, D: int) -> int:
+    """Workspace bytes fsa_mean_bwd_ws can use for this shape (0: it always takes the atomic route)."""
+    return int(lib().fsa_mean_bwd_workspace_bytes(B, k1, k2, D))
+
+
+def fsa_mean_bwd_ws(grad_out: torch.Tensor, ids1: torch.Tensor, ids2: Optional[torch.Tensor] = None,
+                    grad_h1: Optional[torch.Tensor] = None, *, grad_x: torch.Tensor,
+                    workspace: Optional[torch.Tensor] = None,
+                    stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """fsa_mean_bwd with a caller workspace (any contiguous GPU tensor; torch allocations are
+    256-byte aligned): wide-row 2-hop calls then update every destination row once, without atomics."""
+    _need(grad_out, "grad_out", torch.float32); _need(ids1, "ids1", torch.int32)
+    _need(grad_x, "grad_x", torch.float32)
+    B, k1 = ids1.shape
+    D = grad_out.shape[1]
+    N = grad_x.shape[0]
+    if grad_x.shape[1] != D or grad_out.shape[0] != B:
+        raise ValueError("shape mismatch between grad_out, ids1 and grad_x")
+    k2 = 0
+    if ids2 is not None:
+        _need(ids2, "ids2", torch.int32)
+        if ids2.dim() != 3 or tuple(ids2.shape[:2]) != (B, k1):
+            raise ValueError("ids2 must be [B,k1,k2]")
+        k2 = ids2.shape[2]
+    if grad_h1 is not None:
+        _need(grad_h1, "grad_h1", torch.float32)
+        _shape(grad_h1, "grad_h1", (B, k1, D))
+    ws_bytes = 0
+    if workspace is not None:
+        _need(workspace, "workspace")
+        ws_bytes = workspace.numel() * workspace.element_size()
+    _same_device(grad_x, (grad_out, "grad_out"), (grad_h1, "grad_h1"), (ids1, "ids1"), (ids2, "ids2"), (workspace, "workspace"))
+    rc = lib().fsa_mean_bwd_ws(_ptr(grad_out), _ptr(grad_h1), _ptr(ids1), _ptr(ids2), B, k1, k2, D,
+                               _ptr(grad_x), N, _ptr(workspace), ws_bytes, _stream(stream, grad_x))
+    if rc != FSA_OK:
+        raise FsaError(rc, "fsa_mean_bwd_ws")
     return grad_x
 
 

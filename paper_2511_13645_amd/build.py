@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfsa_hip.so")
-SOURCES = ["fsa_api.hip", "fsa_fwd.hip", "fsa_bwd.hip", "fsa_wbwd.hip"]
+SOURCES = ["fsa_api.hip", "fsa_fwd.hip", "fsa_bwd.hip", "fsa_bwd_sorted.hip", "fsa_wbwd.hip"]
 HEADERS = ["fsa_device.hip.h", "fsa_internal.h", "fsa_layout.h", os.path.join("..", "..", "include", "fsa.h")]
 
 HIPCC_FLAGS = [

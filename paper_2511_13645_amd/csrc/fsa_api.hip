@@ -161,6 +161,37 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
     return status_of(fsa::launch_backward(a, static_cast<hipStream_t>(stream)));
 }
 
+int64_t fsa_mean_bwd_workspace_bytes(int64_t B, int32_t k1, int32_t k2, int64_t D) {
+    if (B <= 0 || D <= 0 || !fanout_ok(k1) || !fanout_ok(k2)) return 0;
+    return (int64_t)fsa::sorted_workspace_bytes(B, k1, k2, D);
+}
+
+int fsa_mean_bwd_ws(const float* grad_out, const float* grad_h1,
+                    const int32_t* ids1, const int32_t* ids2,
+                    int64_t B, int32_t k1, int32_t k2, int64_t D,
+                    float* grad_x, int64_t num_nodes,
+                    void* workspace, int64_t workspace_bytes, void* stream) {
+    if (!grad_x) return FSA_ERR_NULL;
+    if (B != 0 && (!grad_out || !ids1)) return FSA_ERR_NULL;
+    if (int rc = check_common(FSA_F32, D, num_nodes, B)) return rc;
+    if (!fanout_ok(k1) || (ids2 && !fanout_ok(k2))) return FSA_ERR_ARG;
+    if (!ids2 && grad_h1) return FSA_ERR_ARG;
+    if (workspace_bytes < 0) return FSA_ERR_ARG;
+    if (!aligned(grad_out, 4) || !aligned(grad_h1, 4) || !aligned(grad_x, 4) || !aligned(ids1, 4) || !aligned(ids2, 4))
+        return FSA_ERR_ALIGN;
+    if (B == 0) return FSA_OK;
+    drop_stale_hip_error();
+
+    fsa::BwdArgs a{};
+    a.grad_out = grad_out; a.grad_h1 = grad_h1; a.ids1 = ids1; a.ids2 = ids2;
+    a.B = B; a.k1 = k1; a.k2 = ids2 ? k2 : 0; a.D = D; a.grad_x = grad_x;
+    bool used = false;
+    if (hipError_t e = fsa::launch_backward_sorted(a, workspace, (size_t)workspace_bytes, static_cast<hipStream_t>(stream), &used))
+        return status_of(e);
+    if (used) return FSA_OK;
+    return status_of(fsa::launch_backward(a, static_cast<hipStream_t>(stream)));
+}
+
 int fsa_mean_bwd_lp(const void* grad_out, const void* grad_h1, int grad_dtype,
                     const int32_t* ids1, const int32_t* ids2,
                     int64_t B, int32_t k1, int32_t k2, int64_t D,

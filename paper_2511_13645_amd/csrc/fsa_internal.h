@@ -69,6 +69,11 @@ hipError_t launch_forward(const FwdArgs& a, hipStream_t stream);
 hipError_t launch_forward_weighted(const FwdArgs& a, const WeightArgs& w, hipStream_t stream);
 hipError_t launch_backward_weighted(const BwdArgs& a, const WeightArgs& w, hipStream_t stream);
 hipError_t launch_backward(const BwdArgs& a, hipStream_t stream);
+// 2-hop backward that owns each destination row (sorted, no atomics on full rows): needs a caller
+// workspace; `*used` tells whether it ran (false: not eligible, nothing was launched).
+size_t sorted_workspace_bytes(int64_t B, int k1, int k2, int64_t D);
+hipError_t launch_backward_sorted(const BwdArgs& a, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                                  bool* used);
 hipError_t launch_backward1_weighted(const BwdArgs& a, const float* w1, hipStream_t stream);   // 1-hop, fp32
 // work[b,j,:] = (slot j took part ? grad_out[b,:] / #such slots : 0) + grad_h1[b,j,:]  (grad_h1 nullable)
 hipError_t launch_deep_grad(const float* grad_out, const float* grad_h1, const int32_t* ids1, const int32_t* ids2,

@@ -27,6 +27,11 @@ def test_device_memory_is_unchanged_across_every_entry_point():
     ids1, ids2, ids3 = z(B, k1, dt=torch.int32), z(B, k1, k2, dt=torch.int32), z(B, k1, k2, k3, dt=torch.int32)
     cnt2, w1, w2 = z(B, k1, dt=torch.int32), z(B, k1), z(B, k1, k2)
     g, gh, gx, gx16, work = z(B, D) + 1, z(B, k1, D) + 1, z(n, D), z(n, D, dt=torch.bfloat16), z(B, k1, D)
+    Dw = 2048                                              # wide rows: 700*6*5 entries x 8 KB take the owning route
+    gw, gxw = z(B, Dw) + 1, z(n, Dw)
+    need = L.fsa_mean_bwd_workspace_bytes(B, k1, k2, Dw)
+    assert need > 0
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
     fan = (ctypes.c_int32 * 3)(k1, k2, k3)
     fp = ctypes.cast(fan, ctypes.c_void_p)
     st = torch.cuda.current_stream().cuda_stream
@@ -38,6 +43,10 @@ def test_device_memory_is_unchanged_across_every_entry_point():
                                                                    P(out), P(h1), P(ids1), P(ids2), st),
         "fsa_mean_replay_fwd": lambda: L.fsa_mean_replay_fwd(P(x), 0, D, n, P(ids1), P(ids2), B, k1, k2, P(out), P(h1), st),
         "fsa_mean_bwd": lambda: L.fsa_mean_bwd(P(g), P(gh), P(ids1), P(ids2), B, k1, k2, D, P(gx), n, st),
+        "fsa_mean_bwd_ws (atomic route)": lambda: L.fsa_mean_bwd_ws(P(g), P(gh), P(ids1), P(ids2), B, k1, k2, D, P(gx), n,
+                                                                    P(ws), ws.numel(), st),
+        "fsa_mean_bwd_ws (owning route)": lambda: L.fsa_mean_bwd_ws(P(gw), None, P(ids1), P(ids2), B, k1, k2, Dw, P(gxw), n,
+                                                                    P(ws), ws.numel(), st),
         "fsa_mean_bwd_lp": lambda: L.fsa_mean_bwd_lp(P(g), P(gh), 0, P(ids1), P(ids2), B, k1, k2, D, P(gx16), 1, n, st),
         "fsa_sample_wmean_fwd": lambda: L.fsa_sample_wmean_fwd(P(indptr), 0, P(indices), P(ew), n, P(x), 0, D, P(seeds), B, fp, 2, 3,
                                                                P(out), P(h1), P(ids1), P(ids2), P(w1), P(w2), st),
