@@ -97,15 +97,17 @@ def traffic_from_counters(args):
     import csv
     fetch_csv, write_csv = args.traffic_from
 
-    def mean_kib(path, counter, needle):
+    def mean_kib(path, counter, needle, largest_only=False):
         v = [float(r["Counter_Value"]) for r in csv.DictReader(open(path))
              if r["Counter_Name"] == counter and needle in r["Kernel_Name"]]
+        if largest_only and v:                   # other, small copies of the run use the same kernel
+            v = [a for a in v if a >= 0.5 * max(v)]
         if not v:
             raise RuntimeError("%s: no %s rows for a kernel named *%s*" % (path, counter, needle))
         return sum(v) / len(v), len(v)
     gib_kib = float(1 << 20)                     # the calibration copy moves 1 GiB each way
-    f_copy, _ = mean_kib(fetch_csv, "FETCH_SIZE", "copyBuffer")
-    w_copy, _ = mean_kib(write_csv, "WRITE_SIZE", "copyBuffer")
+    f_copy, _ = mean_kib(fetch_csv, "FETCH_SIZE", "copyBuffer", largest_only=True)
+    w_copy, _ = mean_kib(write_csv, "WRITE_SIZE", "copyBuffer", largest_only=True)
     f_k, n_f = mean_kib(fetch_csv, "FETCH_SIZE", args.traffic_kernel)
     w_k, n_w = mean_kib(write_csv, "WRITE_SIZE", args.traffic_kernel)
     f_scale, w_scale = gib_kib / f_copy, gib_kib / w_copy
@@ -116,6 +118,49 @@ def traffic_from_counters(args):
     path = os.path.join(ROOT, "profiles", "traffic_%s.json" % args.workload)
     json.dump(out, open(path, "w"), indent=1)
     print(json.dumps(out))
+    return 0
+
+
+def trace_roots(L, binding, synth, torch, w, dev, batches=(4096, 65536)):
+    """--trace-roots (needs --lib with a -DFSA_TRACE build): per-root start, gather-start and end times of
+    the fused 2-hop forward, printed as the distribution of when roots begin to gather and when they finish."""
+    import numpy as np
+    g, x = w.graph, w.x
+    fan = list(w.fanouts)
+    L.fsa_debug_set_trace.argtypes = [ctypes.c_void_p]
+    for B in batches:
+        seeds = synth.seed_batches(g.num_nodes, B, 4, seed=2).to(dev)
+        tr = torch.zeros((B, 4), dtype=torch.int64, device=dev)
+        L.fsa_debug_set_trace(tr.data_ptr())
+        for i in range(4):
+            tr.zero_()
+            binding.fsa_sample_mean_fwd(g.indptr, g.indices, x, seeds[i], fan, w.sampler_seed)
+            torch.cuda.synchronize()
+        L.fsa_debug_set_trace(None)
+        t = tr.cpu().numpy().astype(np.float64)
+        rows = t[:, 3]
+        t0 = t[:, 0].min()
+        st, gs, en = (t[:, 0] - t0) * 0.01, (t[:, 1] - t0) * 0.01, (t[:, 2] - t0) * 0.01      # 10 ns ticks -> us
+        pc = np.percentile
+        print("B=%d: first start to last end %.2f us (stamps add about a fifth); rows per root mean %.1f p50 %.0f p90 %.0f max %.0f"
+              % (B, en.max(), rows.mean(), pc(rows, 50), pc(rows, 90), rows.max()))
+        for name, a in (("wave start", st), ("gather start", gs), ("wave end", en), ("start -> gather", gs - st),
+                        ("gather duration", en - gs)):
+            print("   %-18s p1 %6.2f  p10 %6.2f  p50 %6.2f  p90 %6.2f  p99 %6.2f  max %6.2f us"
+                  % (name, pc(a, 1), pc(a, 10), pc(a, 50), pc(a, 90), pc(a, 99), a.max()))
+        for lo, hi in ((0, 1), (1, 33), (33, 65), (65, 97), (97, 129), (129, 100000)):
+            m = (rows >= lo) & (rows < hi)
+            if m.sum():
+                print("   roots with %3d..%-3d rows: n=%6d  start->gather p50 %5.2f  gather p50 %5.2f p90 %5.2f  end p50 %6.2f p90 %6.2f max %6.2f"
+                      % (lo, min(hi - 1, int(rows.max())), m.sum(), pc((gs - st)[m], 50), pc((en - gs)[m], 50),
+                         pc((en - gs)[m], 90), pc(en[m], 50), pc(en[m], 90), en[m].max()))
+        if B <= 8192:
+            print("   time (us): roots still sampling / roots gathering / rows per us (each root's rows spread evenly over its gather)")
+            for a in np.arange(0, en.max(), 2.0):
+                b_ = a + 2.0
+                ov = np.clip(np.minimum(en, b_) - np.maximum(gs, a), 0, None)
+                print("   %5.0f %6d %6d %9.0f" % (a, ((st < b_) & (gs > a)).sum(), ((gs < b_) & (en > a)).sum(),
+                                                  (rows * ov / np.maximum(en - gs, 1e-9)).sum() / 2.0))
     return 0
 
 
@@ -418,6 +463,12 @@ def main() -> int:
     ap.add_argument("--traffic-from", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
                     help="no GPU work: write profiles/traffic_<workload>.json from two rocprofv3 --pmc counter CSVs")
     ap.add_argument("--traffic-kernel", default="fwd2_kernel", help="kernel name fragment for --traffic-from")
+    ap.add_argument("--only-paths", default="", metavar="NAMES",
+                    help="comma-separated workloads: measure forward, replay forward and backward (also with a "
+                         "workspace) of each at its own batch size, print them as one JSON line and stop")
+    ap.add_argument("--lib", default="", help="load this build of the library instead of libfsa_hip.so (debug builds)")
+    ap.add_argument("--trace-roots", action="store_true",
+                    help="per-root timeline of the 2-hop forward; needs --lib with a build made with -DFSA_TRACE")
     args = ap.parse_args()
     if args.traffic_from:
         return traffic_from_counters(args)
@@ -434,6 +485,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = "cuda:0"
+    if args.lib:
+        binding.LIB_PATH = os.path.abspath(args.lib)
     L = binding.lib()
 
     if args.calibrate_copy:
@@ -461,6 +514,16 @@ def main() -> int:
         ceilings = {"unit": "GB/s", "table_gib": args.ceilings, **{n: vals[i] for i, n in enumerate(names)}}
         log("[bench] ceilings: %s" % json.dumps(ceilings))
 
+    if args.only_paths:
+        res = []
+        for name in args.only_paths.split(","):
+            wk = synth.make_workload(name, device=dev, scale=args.scale)
+            res.append(measure_paths(L, binding, synth, torch, wk, args.batch or wk.batch, dev, n_launch=args.steps if args.steps < 200 else 20))
+            del wk
+            torch.cuda.empty_cache()
+        print(json.dumps({"workloads": res}), flush=True)
+        return 0
+
     t0 = time.time()
     w = load_or_make_workload(args.workload, args.scale, args.cache, dev)
     torch.cuda.synchronize()
@@ -480,6 +543,8 @@ def main() -> int:
         (w.name, N, g.num_edges, D, str(x.dtype), B, fan, time.time() - t0))
 
     steps, warmup = args.steps, args.warmup
+    if args.trace_roots:
+        return trace_roots(L, binding, synth, torch, w, dev)
     if args.three_hop:
         if hops != 2:
             print("bench.py: --three-hop needs a two-hop workload", file=sys.stderr)

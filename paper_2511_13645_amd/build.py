@@ -27,8 +27,9 @@ def hipcc() -> str:
     return "hipcc"
 
 
-def build_hip(extra_flags=(), verbose: bool = False) -> str:
-    """Compile every source to an object (side by side, one hipcc each), then link the library."""
+def build_hip(extra_flags=(), verbose: bool = False, out: str = LIB) -> str:
+    """Compile every source to an object (side by side, one hipcc each), then link the library.
+    `out` names another file for a debug build (e.g. -DFSA_TRACE), so that it never replaces the product."""
     from concurrent.futures import ThreadPoolExecutor
     import shutil
     import tempfile
@@ -43,15 +44,15 @@ def build_hip(extra_flags=(), verbose: bool = False) -> str:
             return obj
         with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
             objs = list(pool.map(compile_one, SOURCES))
-        tmp = LIB + ".tmp.%d" % os.getpid()
+        tmp = out + ".tmp.%d" % os.getpid()
         cmd = [hipcc(), "--offload-arch=gfx950", "-fPIC", "-shared", "-o", tmp, *objs]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True, cwd=CSRC)
-        os.replace(tmp, LIB)
+        os.replace(tmp, out)
     finally:
         shutil.rmtree(work, ignore_errors=True)
-    return LIB
+    return out
 
 
 def is_stale() -> bool:
@@ -62,4 +63,12 @@ def is_stale() -> bool:
 
 
 if __name__ == "__main__":
-    print(build_hip(sys.argv[1:], verbose=True))
+    # python -m paper_2511_13645_amd.build [--out FILE] [extra hipcc flags]; e.g. the debug build whose 2-hop
+    # forward stamps per-root times (bench.py --trace-roots):  --out libfsa_hip_trace.so -DFSA_TRACE
+    argv = sys.argv[1:]
+    target = LIB
+    if "--out" in argv:
+        i = argv.index("--out")
+        target = os.path.join(HERE, os.path.basename(argv[i + 1]))
+        del argv[i:i + 2]
+    print(build_hip(argv, verbose=True, out=target))
