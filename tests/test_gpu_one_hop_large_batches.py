@@ -104,3 +104,32 @@ def test_large_batch_with_negative_seeds_and_saved_ids_with_holes(fsa, orc):
     a, _ = forward_scales(x.to(dev), d_ids, None)
     assert_close(to_f64(out), ref, a, 1e-5, "replay with holes")
     assert float(out[::17].abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("B", [32769, 40003, 65537])
+def test_last_wave_writes_nothing_beyond_the_batch(fsa, B):
+    """Outputs carved out of larger buffers with sentinel words on both sides: the last wave's
+    missing seeds (B is not a multiple of the seeds per wave) leave the sentinels alone, and the
+    carved outputs equal those of an ordinary call."""
+    n, D, k, G = 3000, 32, 15, 4096
+    indptr, indices = ragged_graph(n, seed=B % 97, max_deg=40)
+    dev = "cuda:0"
+    d_indptr, d_indices = torch.from_numpy(indptr).to(dev), torch.from_numpy(indices).to(dev)
+    x = torch.randn((n, D), generator=torch.Generator().manual_seed(2)).to(dev)
+    seeds = torch.from_numpy(np.random.default_rng(B).integers(0, n, B).astype(np.int32)).to(dev)
+    want = fsa.fsa_sample_mean_fwd(d_indptr, d_indices, x, seeds, [k], 19)
+    buf_out = torch.full((G + B * D + G,), -7.5, dtype=torch.float32, device=dev)
+    buf_ids = torch.full((G + B * k + G,), -12345, dtype=torch.int32, device=dev)
+    out = buf_out[G:G + B * D].view(B, D)
+    ids = buf_ids[G:G + B * k].view(B, k)
+    fsa.fsa_sample_mean_fwd(d_indptr, d_indices, x, seeds, [k], 19, out=out, out_ids1=ids)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want[0]) and torch.equal(ids, want[2])
+    for buf, fill in ((buf_out, -7.5), (buf_ids, -12345)):
+        assert bool((buf[:G] == fill).all()) and bool((buf[-G:] == fill).all())
+    # replay from the carved IDs, outputs carved again
+    buf_out.fill_(-7.5)
+    fsa.fsa_mean_replay_fwd(x, ids, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want[0])
+    assert bool((buf_out[:G] == -7.5).all()) and bool((buf_out[-G:] == -7.5).all())

@@ -57,10 +57,10 @@ def test_layerwise_two_hop(fsa, orc, dtype):
     assert_close(to_f64(m1), r_m1, a_m1, TOL3[dtype], "out_m1")
 
 
-def three_hop_case(fsa, orc, indptr, indices, x, seeds, fan, seed, what, check_bwd=True):
+def three_hop_case(fsa, orc, indptr, indices, x, seeds, fan, seed, what, check_bwd=True, tol=None):
     n, D = x.shape
     B = len(seeds)
-    tol = TOL3[x.dtype]
+    tol = TOL3[x.dtype] if tol is None else tol
     hx, is_bf16 = _oracle_x(x)
     ref = orc.sample_mean3_fwd(indptr, indices, hx, seeds, fan, seed, bf16=is_bf16)
     d_indptr, d_indices = _dev_graph(indptr, indices)
@@ -145,6 +145,29 @@ def test_three_hop_fanout_range(fsa, orc, fan):
     x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32))
     seeds = np.concatenate([np.arange(8), rng.integers(0, n, B - 8)]).astype(np.int32)
     three_hop_case(fsa, orc, indptr, indices, x, seeds, fan, 17, "3-hop fan=%s" % fan)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_three_hop_twenty_slots(fsa, orc, dtype):
+    """k1 = 20 hop-1 slots per seed, B * k1 = 2400 roots of the inner launch."""
+    n, D, B, fan = 2500, 72, 120, [20, 4, 3]
+    indptr, indices = ragged_graph(n, seed=79, max_deg=50, hub_deg=600)
+    rng = np.random.default_rng(80)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32)).to(dtype)
+    seeds = np.concatenate([np.arange(8), rng.integers(0, n, B - 8)]).astype(np.int32)
+    three_hop_case(fsa, orc, indptr, indices, x, seeds, fan, 5, "3-hop k1=20 %s" % dtype)
+
+
+@pytest.mark.parametrize("D,dtype", [(602, torch.float32), (1024, torch.bfloat16), (1205, torch.float32)])
+def test_three_hop_wide_rows(fsa, orc, D, dtype):
+    """Rows of several 64-lane tiles (the multi-tile gather: 5 tiles, 2 tiles) and of more tiles
+    than that gather takes (19 tiles of 4-byte chunks, walked tile by tile)."""
+    n, B, fan = 1200, 60, [6, 5, 4]
+    indptr, indices = ragged_graph(n, seed=D, max_deg=30, hub_deg=300)
+    rng = np.random.default_rng(D)
+    x = torch.from_numpy(rng.standard_normal((n, D)).astype(np.float32)).to(dtype)
+    seeds = np.concatenate([np.arange(8), rng.integers(0, n, B - 8)]).astype(np.int32)
+    three_hop_case(fsa, orc, indptr, indices, x, seeds, fan, 21, "3-hop D=%d" % D)
 
 
 def test_three_hop_empty_batch_and_degenerate_graph(fsa, orc):
