@@ -133,7 +133,8 @@ int fsa_mean_bwd(const float* grad_out, const float* grad_h1,
  * The atomic backward is bound by the L2 atomic unit (one 4-byte add per channel and clock), and
  * that cost grows with the row width.  Given a workspace, 2-hop calls with wide rows
  * (at least 1024 bytes, at most 8 x 64 chunks of 16 / 8 / 4 bytes -- the widest the row size and
- * the pointers' alignment allow -- and at least 32 MiB of row updates per call) take another route: the
+ * the pointers' alignment allow -- and at least 32 MiB of row updates per call), and calls with
+ * rows of 256 .. 1023 bytes and at least 393,216 leaf slots (B*k1*k2), take another route: the
  * leaf entries are binned by destination row, each bin is sorted in LDS, the gradients that reach
  * one row are summed in registers and the row is updated once with plain loads and stores by the
  * one workgroup that owns it (Sec. 3.3 only fixes WHICH rows receive gradient; how is ours).

@@ -1,5 +1,5 @@
-// 2-hop backward without atomics on the feature rows, for wide rows and a caller workspace
-// (fsa_mean_bwd_ws).  The paper describes no backward kernel (Sec. 3.3 "Reproducibility" only
+// 2-hop backward without atomics on the feature rows, for wide rows (or large batches of rows
+// of 256 bytes and more) and a caller workspace (fsa_mean_bwd_ws).  The paper describes no backward kernel (Sec. 3.3 "Reproducibility" only
 // asks that the saved IDs are replayed); this is the second design of this library.
 //
 // Why: a hardware fp32 atomic is one 4-byte operation per L2 channel and clock, so the atomic
@@ -149,6 +149,84 @@ template <int VE, typename T> __device__ __forceinline__ T add_chunk(const T& v,
     return r;
 }
 
+// Loads bucket `bucket`'s entries into `keys`, sorts them ascending -- (row, slot) order fixes the
+// order of every later sum -- and lists the first entry of every distinct row in `heads`.
+// Returns the number of entries (at most kBucketCap); *overflowed: more were appended than the
+// bucket holds, the rest are in the overflow list.  Called by all threads of the workgroup.
+__device__ __forceinline__ int sort_bucket(const SortedParams& p, int bucket, unsigned long long* keys, int* heads,
+                                           int* n_heads, bool* overflowed) {
+    const int tid = threadIdx.x;
+    int n = p.ws.cursor[(size_t)bucket * kCursorStride];
+    *overflowed = n > kBucketCap;
+    if (n > kBucketCap) n = kBucketCap;
+    if (tid == 0) *n_heads = 0;
+    if (n == 0) return 0;                                             // workgroup-uniform
+    int npow = 64;
+    while (npow < n) npow <<= 1;                                      // <= kBucketCap
+    const unsigned long long* src = p.ws.pairs + (size_t)bucket * kBucketCap;
+    for (int i = tid; i < npow; i += blockDim.x) keys[i] = i < n ? src[i] : ~0ull;
+    __syncthreads();
+    if (npow <= kRankSortMax) {
+        // short lists (the usual case): every entry counts the entries that go before it --
+        // one pass of LDS broadcast reads and a single barrier instead of a barrier per stage
+        unsigned long long mine = ~0ull;
+        int rank = 0;
+        if (tid < n) {
+            mine = keys[tid];
+            for (int j = 0; j < n; ++j) {
+                const unsigned long long other = keys[j];
+                rank += (other < mine) || (other == mine && j < tid);
+            }
+        }
+        __syncthreads();
+        if (tid < n) keys[rank] = mine;
+        __syncthreads();
+    } else {
+        for (int k = 2; k <= npow; k <<= 1) {                         // bitonic network
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int i = tid; i < npow; i += blockDim.x) {
+                    const int x = i ^ j;
+                    if (x > i) {
+                        const unsigned long long a = keys[i], c = keys[x];
+                        const bool up = (i & k) == 0;
+                        if ((a > c) == up) { keys[i] = c; keys[x] = a; }
+                    }
+                }
+                __syncthreads();
+            }
+        }
+    }
+    for (int i = tid; i < n; i += blockDim.x) {
+        if (i == 0 || (uint32_t)(keys[i] >> 32) != (uint32_t)(keys[i - 1] >> 32)) heads[atomicAdd(n_heads, 1)] = i;
+    }
+    __syncthreads();
+    return n;
+}
+
+// Overflow entries (a bucket holds kBucketCap; rows sampled thousands of times in one batch,
+// hubs, fill theirs): shared out over all waves of the grid and added with hardware atomics,
+// one element per lane, as the other backward does.  All entries of a row hash to one bucket,
+// so only rows of buckets that overflowed receive such adds -- and those buckets' own sums
+// went in by atomics too, never by plain stores.
+__device__ __forceinline__ void add_overflow_entries(const SortedParams& p, int bucket, int wave, int lane) {
+    const int n_over = *p.ws.overflow_count;
+    if (n_over <= 0) return;                                          // grid-uniform
+    const int total_waves = gridDim.x * (blockDim.x >> 6);
+    for (int o = bucket * (int)(blockDim.x >> 6) + wave; o < n_over; o += total_waves) {
+        const unsigned long long key = p.ws.overflow[o];
+        const uint32_t row = (uint32_t)(key >> 32), s = (uint32_t)key;
+        const float2 cf = p.ws.coef[s];
+        const float* go = p.grad_out + (int64_t)(s / (uint32_t)p.k1) * p.D;
+        const float* gh = p.grad_h1 ? p.grad_h1 + (int64_t)s * p.D : nullptr;
+        float* dst = p.grad_x + (int64_t)row * p.D;
+        for (int64_t d = lane; d < p.D; d += kWave) {
+            float v = cf.x * go[d];
+            if (gh) v = fmaf(cf.y, gh[d], v);
+            unsafeAtomicAdd(dst + d, v);
+        }
+    }
+}
+
 // One workgroup (4 waves) per bucket.  MT: row tiles of 64 lanes x VB bytes kept in registers.
 template <int VB, int MT>
 __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const SortedParams p) {
@@ -163,52 +241,9 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const Sor
     const int bucket = blockIdx.x;
     const int k1 = p.k1;
     const int tiles = (p.chunks + kWave - 1) >> 6;                    // <= MT, checked on the host
-    int n = p.ws.cursor[(size_t)bucket * kCursorStride];
-    const bool overflowed = n > kBucketCap;                           // some of this bucket's entries are in the overflow list
-    if (overflowed) n = kBucketCap;
-    if (tid == 0) n_heads = 0;
+    bool overflowed;                                                  // some of this bucket's entries are in the overflow list
+    const int n = sort_bucket(p, bucket, keys, heads, &n_heads, &overflowed);
     if (n > 0) {                                                      // workgroup-uniform
-        int npow = 64;
-        while (npow < n) npow <<= 1;                                  // <= kBucketCap
-        const unsigned long long* src = p.ws.pairs + (size_t)bucket * kBucketCap;
-        for (int i = tid; i < npow; i += blockDim.x) keys[i] = i < n ? src[i] : ~0ull;
-        __syncthreads();
-        // sort ascending: (row, slot) order fixes the order of every later sum
-        if (npow <= kRankSortMax) {
-            // short lists (the usual case): every entry counts the entries that go before it --
-            // one pass of LDS broadcast reads and a single barrier instead of a barrier per stage
-            unsigned long long mine = ~0ull;
-            int rank = 0;
-            if (tid < n) {
-                mine = keys[tid];
-                for (int j = 0; j < n; ++j) {
-                    const unsigned long long other = keys[j];
-                    rank += (other < mine) || (other == mine && j < tid);
-                }
-            }
-            __syncthreads();
-            if (tid < n) keys[rank] = mine;
-            __syncthreads();
-        } else {
-            for (int k = 2; k <= npow; k <<= 1) {                     // bitonic network
-                for (int j = k >> 1; j > 0; j >>= 1) {
-                    for (int i = tid; i < npow; i += blockDim.x) {
-                        const int x = i ^ j;
-                        if (x > i) {
-                            const unsigned long long a = keys[i], c = keys[x];
-                            const bool up = (i & k) == 0;
-                            if ((a > c) == up) { keys[i] = c; keys[x] = a; }
-                        }
-                    }
-                    __syncthreads();
-                }
-            }
-        }
-        // the first entry of every distinct row
-        for (int i = tid; i < n; i += blockDim.x) {
-            if (i == 0 || (uint32_t)(keys[i] >> 32) != (uint32_t)(keys[i - 1] >> 32)) heads[atomicAdd(&n_heads, 1)] = i;
-        }
-        __syncthreads();
         const int nh = n_heads;
         for (int h = wave; h < nh; h += (int)(blockDim.x >> 6)) {     // wave-uniform
             const int i0 = heads[h];
@@ -272,37 +307,78 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const Sor
             }
         }
     }
-    // Overflow entries (a bucket holds kBucketCap; rows sampled thousands of times in one batch,
-    // hubs, fill theirs): shared out over all waves of the grid and added with hardware atomics,
-    // one element per lane, as the other backward does.  All entries of a row hash to one bucket,
-    // so only rows of buckets that overflowed receive such adds -- and those buckets' own sums
-    // went in by atomics above, never by plain stores.
-    const int n_over = *p.ws.overflow_count;
-    if (n_over > 0) {                                                 // grid-uniform
-        const int total_waves = gridDim.x * (blockDim.x >> 6);
-        for (int o = bucket * (int)(blockDim.x >> 6) + wave; o < n_over; o += total_waves) {
-            const unsigned long long key = p.ws.overflow[o];
-            const uint32_t row = (uint32_t)(key >> 32), s = (uint32_t)key;
-            const float2 cf = p.ws.coef[s];
-            const float* go = p.grad_out + (int64_t)(s / (uint32_t)k1) * p.D;
-            const float* gh = p.grad_h1 ? p.grad_h1 + (int64_t)s * p.D : nullptr;
-            float* dst = p.grad_x + (int64_t)row * p.D;
-            for (int64_t d = lane; d < p.D; d += kWave) {
-                float v = cf.x * go[d];
-                if (gh) v = fmaf(cf.y, gh[d], v);
-                unsafeAtomicAdd(dst + d, v);
+    add_overflow_entries(p, bucket, wave, lane);
+}
+
+// The same for rows of at most 64 chunks (under 1 KB): groups of `1 << sub_shift` lanes take a
+// distinct row each, so a workgroup works on 4 .. 64 rows at a time, and a row's old value is
+// requested before its gradients are summed: with rows this short the kernel is bound by the
+// number of dependent memory round trips per wave, not by bytes.
+template <int VB>
+__global__ __launch_bounds__(kSortedThreads) void sorted_reduce_narrow_kernel(const SortedParams p, int sub_shift) {
+    using T = typename FloatChunk<VB>::T;
+    constexpr int VE = FloatChunk<VB>::VE;
+    __shared__ unsigned long long keys[kBucketCap];
+    __shared__ int heads[kBucketCap];
+    __shared__ int n_heads;
+    const int tid = threadIdx.x;
+    const int bucket = blockIdx.x;
+    bool overflowed;
+    const int n = sort_bucket(p, bucket, keys, heads, &n_heads, &overflowed);
+    if (n > 0) {                                                      // workgroup-uniform
+        const int nh = n_heads;
+        const int grp = tid >> sub_shift, sl = tid & ((1 << sub_shift) - 1);
+        const int n_grp = kSortedThreads >> sub_shift;
+        const bool live = sl < p.chunks;
+        for (int h = grp; h < nh; h += n_grp) {                       // uniform within a group of lanes
+            const int i0 = heads[h];
+            const uint32_t row = (uint32_t)(keys[i0] >> 32);
+            float* dst_f = p.grad_x + (int64_t)row * p.D;
+            T* dst = reinterpret_cast<T*>(dst_f);
+            T old{};
+            if (live && !overflowed) old = dst[sl];
+            float acc[VE];
+#pragma unroll
+            for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
+            for (int i = i0; i < n && (uint32_t)(keys[i] >> 32) == row; ++i) {
+                const uint32_t s = (uint32_t)keys[i];
+                const float2 cf = p.ws.coef[s];
+                if (live) {
+                    const T a = reinterpret_cast<const T*>(p.grad_out + (int64_t)(s / (uint32_t)p.k1) * p.D)[sl];
+                    if (p.grad_h1) {
+                        const T c = reinterpret_cast<const T*>(p.grad_h1 + (int64_t)s * p.D)[sl];
+                        fma_chunk<VE>(acc, a, cf.x);
+                        fma_chunk<VE>(acc, c, cf.y);
+                    } else {
+                        fma_chunk<VE>(acc, a, cf.x);
+                    }
+                }
+            }
+            if (live) {
+                if (overflowed) {                                     // see sorted_reduce_kernel
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) unsafeAtomicAdd(dst_f + (int64_t)sl * VE + e, acc[e]);
+                } else {
+                    dst[sl] = add_chunk<VE>(old, acc);
+                }
             }
         }
     }
+    add_overflow_entries(p, bucket, tid >> 6, tid & 63);
 }
 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
 // The path pays when rows are wide (the per-row cost of the atomic unit grows with the row, the
-// three launches and the binning do not) and the batch moves enough bytes to hide them.
+// three launches and the binning do not) and the batch moves enough bytes to hide them.  Rows
+// under 1 KB gain less -- every leaf re-reads its slot's gradient rows, which the atomic backward
+// reads once per slot -- and only in large batches: D=128, 614 k leaves, 121 -> 102 us; D=100,
+// 614 k leaves, 237 -> 210 us; but 154 k leaves, 64 -> 75 us.
 constexpr int64_t kSortedMinRowBytes = 1024;
 constexpr int64_t kSortedMinPayload = 32ll << 20;
+constexpr int64_t kSortedNarrowMinRowBytes = 256;
+constexpr int64_t kSortedNarrowMinEntries = 384 * 1024;
 
 static int sorted_vec_bytes(const BwdArgs& a) {
     auto al = [](const void* q, uintptr_t m) { return q == nullptr || (reinterpret_cast<uintptr_t>(q) % m) == 0; };
@@ -312,8 +388,12 @@ static int sorted_vec_bytes(const BwdArgs& a) {
 }
 
 bool sorted_backward_shape_ok(int64_t B, int k1, int k2, int64_t D) {
-    if (k2 <= 0 || D * 4 < kSortedMinRowBytes) return false;
-    if (B * k1 * k2 * D * 4 < kSortedMinPayload) return false;
+    if (k2 <= 0 || D * 4 < kSortedNarrowMinRowBytes) return false;
+    if (D * 4 < kSortedMinRowBytes) {
+        if (B * k1 * k2 < kSortedNarrowMinEntries) return false;
+    } else if (B * k1 * k2 * D * 4 < kSortedMinPayload) {
+        return false;
+    }
     if (B * k1 * k2 > (int64_t)INT32_MAX) return false;
     return D <= (int64_t)kSortedMaxTiles * kWave * 4;                 // fits the register tiles with 16-byte chunks
                                                                       // (the launch checks the real chunk width)
@@ -358,6 +438,15 @@ hipError_t launch_backward_sorted(const BwdArgs& a, void* workspace, size_t work
     const int P = 1 << lp;
     hipLaunchKernelGGL(sorted_clear_kernel, dim3((P + 255) / 256), dim3(256), 0, stream, p.ws.cursor, P, p.ws.overflow_count);
     hipLaunchKernelGGL(sorted_bin_kernel, dim3((unsigned)a.B), dim3(256), 0, stream, p);
+    if (a.D * 4 < kSortedMinRowBytes && chunks <= kWave) {
+        int sub_shift = 2;
+        while ((1 << sub_shift) < chunks) ++sub_shift;                // 4 .. 64 lanes per row
+        if (vb == 16)     hipLaunchKernelGGL((sorted_reduce_narrow_kernel<16>), dim3(P), dim3(kSortedThreads), 0, stream, p, sub_shift);
+        else if (vb == 8) hipLaunchKernelGGL((sorted_reduce_narrow_kernel<8>), dim3(P), dim3(kSortedThreads), 0, stream, p, sub_shift);
+        else              hipLaunchKernelGGL((sorted_reduce_narrow_kernel<4>), dim3(P), dim3(kSortedThreads), 0, stream, p, sub_shift);
+        *used = true;
+        return hipGetLastError();
+    }
 #define FSA_LAUNCH_SORTED(VB_)                                                                              \
     do {                                                                                                    \
         if (tiles <= 2)      hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 2>), dim3(P), dim3(kSortedThreads), 0, stream, p); \

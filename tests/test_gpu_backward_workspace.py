@@ -1,6 +1,7 @@
 """fsa_mean_bwd_ws: the 2-hop backward that owns every destination row (bins by row, sorts in
 LDS, one plain update per distinct row) against the oracle's backward and against the atomic
-backward, on wide-row shapes that take that route and on shapes that must fall back."""
+backward, on wide-row shapes and large batches of narrower rows that take that route and on
+shapes that must fall back."""
 import numpy as np
 import pytest
 import torch
@@ -91,7 +92,20 @@ def test_a_hub_overflows_its_bin(fsa, orc):
     _check(fsa, orc, 600, 20, 10, 300, 2000, 3, targets=targets)
 
 
-@pytest.mark.parametrize("shape", [(64, 5, 4, 602), (4096, 15, 10, 100), (512, 10, 0, 602)])
+@pytest.mark.parametrize("D", [64, 100, 128, 130, 200, 255])
+def test_large_batches_of_narrow_rows_take_the_owning_route(fsa, orc, D):
+    # rows of 256 .. 1020 bytes: groups of 16 / 32 / 64 lanes per row (D=64: 16 chunks of 16 bytes; 100: 25; 128: 32;
+    # 130: 65 chunks of 8 bytes, more than one wave's lanes -> the wide-row kernel; 200: 50; 255: 4-byte chunks -> wide-row kernel)
+    B, k1, k2 = 4096, 10, 10                                       # 409,600 leaf slots
+    _check(fsa, orc, B, k1, k2, D, 50000, D, with_h1=(D != 200))
+
+
+def test_narrow_rows_with_a_hub_overflowing_its_bin(fsa, orc):
+    targets = np.concatenate([np.full(3000, 9, dtype=np.int32), np.arange(100, 20000, dtype=np.int32)])
+    _check(fsa, orc, 4096, 10, 10, 96, 20000, 4, targets=targets)
+
+
+@pytest.mark.parametrize("shape", [(64, 5, 4, 602), (1024, 15, 10, 100), (8192, 10, 10, 48), (512, 10, 0, 602)])
 def test_small_narrow_and_one_hop_calls_fall_back_to_atomics(fsa, orc, shape):
     B, k1, k2, D = shape
     if k2 == 0:                                                    # 1-hop
