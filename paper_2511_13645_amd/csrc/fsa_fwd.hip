@@ -63,6 +63,13 @@ struct FwdParams {
 #define FSA_STAMP(var) do { } while (0)
 #endif
 
+// A value every lane of the wave holds, moved to scalar registers.
+__device__ __forceinline__ int64_t wave_uniform(int64_t v) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)(uint64_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // Row start and length of node i: both indptr entries are requested before either is used.
 __device__ __forceinline__ void row_extent(const FwdParams& p, int64_t i, int64_t& start, int64_t& deg) {
     int64_t lo, hi;
@@ -92,7 +99,10 @@ __device__ __forceinline__ int hop0_id(const FwdParams& p, int64_t b, int lane, 
     } else {
         // a negative seed (an unused slot of the level above, when calls are chained) is an
         // empty row: nothing is read for it
-        const int64_t r = p.seeds[b];
+        // b is the same in every lane of the wave: saying so lets the seed and its indptr pair come
+        // through the scalar data path, ahead of the vector memory queue
+        const int64_t bu = wave_uniform(b);
+        const int64_t r = wave_uniform((int64_t)p.seeds[bu]);
         const bool active = lane < p.k1;
         int64_t s, deg;
         row_extent(p, r >= 0 ? r : 0, s, deg);
