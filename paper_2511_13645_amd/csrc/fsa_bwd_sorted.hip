@@ -28,14 +28,18 @@
 
 namespace fsa {
 
-constexpr int kBucketCap = 512;           // entries a bucket holds (4 KB of keys in LDS)
-constexpr int kBucketFill = 64;           // expected entries per bucket when every slot is full: small buckets
-                                          // mean many workgroups (occupancy, balance) and short sorts
+constexpr int kBucketCap = 256;           // entries a bucket holds (2 KB of keys in LDS)
+constexpr int kBucketFill = 32;           // expected entries per bucket when every slot is full: small buckets
+                                          // mean many workgroups (balance: 16 / 32 / 64 / 128 per bucket measured
+                                          // 232 / 230 / 237 / 251 us on the social shape) and short sorts
+constexpr int kBucketFillNarrow = 64;     // rows under kSortedWideRowBytes: several rows per wave want more rows
+                                          // per workgroup (D=128, 614 k leaves: 102 us against 108 with 32)
+constexpr int64_t kSortedWideRowBytes = 1024;
 constexpr int kSortedThreads = 256;       // threads of a reduce workgroup
 constexpr int kCursorStride = 32;         // ints between two bucket cursors: one 128-byte line each, so that the
                                           // binning's atomics spread over all L2 channels
 constexpr int kSortedMaxTiles = 8;        // row tiles of 64 lanes held in registers
-constexpr int kRankSortMax = kSortedThreads;     // lists up to one entry per thread are sorted by counting
+static_assert(kBucketCap <= kSortedThreads, "the counting sort gives every entry a thread");
 
 struct SortedWs {                          // carved out of the caller's workspace
     int* cursor;                           // [P * kCursorStride] entries appended to each bucket (may exceed the capacity)
@@ -53,16 +57,16 @@ struct SortedParams {
     int chunks;                            // row chunks of VB bytes
 };
 
-static int sorted_log_p(int64_t B, int k1, int k2) {
+static int sorted_log_p(int64_t B, int k1, int k2, int64_t D) {
     const int64_t entries = B * k1 * k2;
+    const int fill = D * 4 < kSortedWideRowBytes ? kBucketFillNarrow : kBucketFill;
     int lp = 6;
-    while (lp < 18 && ((int64_t)kBucketFill << lp) < entries) ++lp;
+    while (lp < 18 && ((int64_t)fill << lp) < entries) ++lp;
     return lp;
 }
 
-// Byte offsets of the workspace parts (each 256-byte aligned) and the total.
-static void sorted_layout(int64_t B, int k1, int k2, size_t off[5], size_t& total, int& log_p) {
-    log_p = sorted_log_p(B, k1, k2);
+static void sorted_layout(int64_t B, int k1, int k2, int64_t D, size_t off[5], size_t& total, int& log_p) {
+    log_p = sorted_log_p(B, k1, k2, D);
     const size_t P = (size_t)1 << log_p;
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
     size_t o = 0;
@@ -161,14 +165,12 @@ __device__ __forceinline__ int sort_bucket(const SortedParams& p, int bucket, un
     if (n > kBucketCap) n = kBucketCap;
     if (tid == 0) *n_heads = 0;
     if (n == 0) return 0;                                             // workgroup-uniform
-    int npow = 64;
-    while (npow < n) npow <<= 1;                                      // <= kBucketCap
     const unsigned long long* src = p.ws.pairs + (size_t)bucket * kBucketCap;
-    for (int i = tid; i < npow; i += blockDim.x) keys[i] = i < n ? src[i] : ~0ull;
+    if (tid < n) keys[tid] = src[tid];
     __syncthreads();
-    if (npow <= kRankSortMax) {
-        // short lists (the usual case): every entry counts the entries that go before it --
-        // one pass of LDS broadcast reads and a single barrier instead of a barrier per stage
+    {
+        // every entry counts the entries that go before it: one pass of LDS broadcast reads and a
+        // single barrier (a bucket holds at most one entry per thread)
         unsigned long long mine = ~0ull;
         int rank = 0;
         if (tid < n) {
@@ -181,20 +183,6 @@ __device__ __forceinline__ int sort_bucket(const SortedParams& p, int bucket, un
         __syncthreads();
         if (tid < n) keys[rank] = mine;
         __syncthreads();
-    } else {
-        for (int k = 2; k <= npow; k <<= 1) {                         // bitonic network
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                for (int i = tid; i < npow; i += blockDim.x) {
-                    const int x = i ^ j;
-                    if (x > i) {
-                        const unsigned long long a = keys[i], c = keys[x];
-                        const bool up = (i & k) == 0;
-                        if ((a > c) == up) { keys[i] = c; keys[x] = a; }
-                    }
-                }
-                __syncthreads();
-            }
-        }
     }
     for (int i = tid; i < n; i += blockDim.x) {
         if (i == 0 || (uint32_t)(keys[i] >> 32) != (uint32_t)(keys[i - 1] >> 32)) heads[atomicAdd(n_heads, 1)] = i;
@@ -240,12 +228,24 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const Sor
     const int wave = tid >> 6;
     const int bucket = blockIdx.x;
     const int k1 = p.k1;
-    const int tiles = (p.chunks + kWave - 1) >> 6;                    // <= MT, checked on the host
+    const int tiles = (p.chunks + kWave - 1) >> 6;
+    const int parts = (tiles + MT - 1) / MT;                          // a row is summed in `parts` pieces of MT tiles,
+                                                                      // each by whichever wave comes to it
+    __shared__ int next_item;
+    if (tid == 0) next_item = 0;                                      // sort_bucket's barriers come before its first use
     bool overflowed;                                                  // some of this bucket's entries are in the overflow list
     const int n = sort_bucket(p, bucket, keys, heads, &n_heads, &overflowed);
     if (n > 0) {                                                      // workgroup-uniform
         const int nh = n_heads;
-        for (int h = wave; h < nh; h += (int)(blockDim.x >> 6)) {     // wave-uniform
+        // a wave takes the next piece of work when it is free (rows differ in how many entries
+        // reach them: fixed shares would leave three waves waiting for the one with a hub row)
+        for (;;) {
+            int item = 0;
+            if (lane == 0) item = atomicAdd(&next_item, 1);
+            item = __builtin_amdgcn_readfirstlane(item);
+            if (item >= nh * parts) break;                            // wave-uniform
+            const int h = item / parts;
+            const int tile0 = (item - h * parts) * MT;
             const int i0 = heads[h];
             const uint32_t row = (uint32_t)(keys[i0] >> 32);
             float* dst_f = p.grad_x + (int64_t)row * p.D;
@@ -264,16 +264,16 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const Sor
                 T a[MT], c[MT];
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    const int chunk = t * kWave + lane;
-                    if (t < tiles && chunk < p.chunks) {
+                    const int chunk = (tile0 + t) * kWave + lane;
+                    if (chunk < p.chunks) {
                         a[t] = go[chunk];
                         if (gh) c[t] = gh[chunk];
                     }
                 }
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    const int chunk = t * kWave + lane;
-                    if (t < tiles && chunk < p.chunks) {
+                    const int chunk = (tile0 + t) * kWave + lane;
+                    if (chunk < p.chunks) {
                         fma_chunk<VE>(acc[t], a[t], cf.x);
                         if (gh) fma_chunk<VE>(acc[t], c[t], cf.y);
                     }
@@ -284,25 +284,26 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_kernel(const Sor
                 // atomics at the same time: the sums of a full bucket go in by atomics as well
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    const int chunk = t * kWave + lane;
-                    if (t < tiles && chunk < p.chunks) {
+                    const int chunk = (tile0 + t) * kWave + lane;
+                    if (chunk < p.chunks) {
 #pragma unroll
                         for (int e = 0; e < VE; ++e) unsafeAtomicAdd(dst_f + (int64_t)chunk * VE + e, acc[t][e]);
                     }
                 }
             } else {
                 // the row is read right before it is written back: the write finds its DRAM page
-                // still open (requesting it before the gradients are summed measured 15 % slower)
+                // still open (requesting it before the first entry's gradients measured 15 % slower,
+                // together with the last entry's 8 %)
                 T old[MT];
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    const int chunk = t * kWave + lane;
-                    if (t < tiles && chunk < p.chunks) old[t] = dst[chunk];
+                    const int chunk = (tile0 + t) * kWave + lane;
+                    if (chunk < p.chunks) old[t] = dst[chunk];
                 }
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    const int chunk = t * kWave + lane;
-                    if (t < tiles && chunk < p.chunks) dst[chunk] = add_chunk<VE>(old[t], acc[t]);
+                    const int chunk = (tile0 + t) * kWave + lane;
+                    if (chunk < p.chunks) dst[chunk] = add_chunk<VE>(old[t], acc[t]);
                 }
             }
         }
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_narrow_kernel(co
             float* dst_f = p.grad_x + (int64_t)row * p.D;
             T* dst = reinterpret_cast<T*>(dst_f);
             T old{};
-            if (live && !overflowed) old = dst[sl];
+            if (live && !overflowed) old = dst[sl];                   // (after the sums: 2 % slower here)
             float acc[VE];
 #pragma unroll
             for (int e = 0; e < VE; ++e) acc[e] = 0.0f;
@@ -375,7 +376,7 @@ __global__ __launch_bounds__(kSortedThreads) void sorted_reduce_narrow_kernel(co
 // under 1 KB gain less -- every leaf re-reads its slot's gradient rows, which the atomic backward
 // reads once per slot -- and only in large batches: D=128, 614 k leaves, 121 -> 102 us; D=100,
 // 614 k leaves, 237 -> 210 us; but 154 k leaves, 64 -> 75 us.
-constexpr int64_t kSortedMinRowBytes = 1024;
+constexpr int64_t kSortedMinRowBytes = kSortedWideRowBytes;
 constexpr int64_t kSortedMinPayload = 32ll << 20;
 constexpr int64_t kSortedNarrowMinRowBytes = 256;
 constexpr int64_t kSortedNarrowMinEntries = 384 * 1024;
@@ -403,7 +404,7 @@ size_t sorted_workspace_bytes(int64_t B, int k1, int k2, int64_t D) {
     if (!sorted_backward_shape_ok(B, k1, k2, D)) return 0;
     size_t off[5], total;
     int lp;
-    sorted_layout(B, k1, k2, off, total, lp);
+    sorted_layout(B, k1, k2, D, off, total, lp);
     return total;
 }
 
@@ -417,7 +418,7 @@ hipError_t launch_backward_sorted(const BwdArgs& a, void* workspace, size_t work
     if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return hipSuccess;
     size_t off[5], total;
     int lp;
-    sorted_layout(a.B, a.k1, a.k2, off, total, lp);
+    sorted_layout(a.B, a.k1, a.k2, a.D, off, total, lp);
     if (workspace_bytes < total) return hipSuccess;
     const int vb = sorted_vec_bytes(a);
     const int chunks = (int)(a.D * 4 / vb);
@@ -447,12 +448,17 @@ hipError_t launch_backward_sorted(const BwdArgs& a, void* workspace, size_t work
         *used = true;
         return hipGetLastError();
     }
+    // tiles of a row summed by one wave at a time: few, so that the kernel's registers allow 8 waves
+    // per SIMD -- it is bound by dependent round trips per wave, which only more waves hide
+    const int mt_t = tune_int("FSA_SORTED_MT", kSortedMaxTiles);
+    const int mt = tiles < mt_t ? tiles : mt_t;
 #define FSA_LAUNCH_SORTED(VB_)                                                                              \
     do {                                                                                                    \
-        if (tiles <= 2)      hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 2>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
-        else if (tiles <= 4) hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 4>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
-        else if (tiles <= 6) hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 6>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
-        else                 hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 8>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
+        if (mt <= 1)      hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 1>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
+        else if (mt <= 2) hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 2>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
+        else if (mt <= 4) hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 4>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
+        else if (mt <= 6) hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 6>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
+        else              hipLaunchKernelGGL((sorted_reduce_kernel<VB_, 8>), dim3(P), dim3(kSortedThreads), 0, stream, p); \
     } while (0)
     if (vb == 16) FSA_LAUNCH_SORTED(16);
     else if (vb == 8) FSA_LAUNCH_SORTED(8);
