@@ -30,6 +30,56 @@ def _build(name):
     return w, seeds
 
 
+_HOST = {}
+
+
+def _host(w):
+    """Host copies of a workload's graph and table for the oracle (made once per workload)."""
+    if _HOST.get("graph") is not w.graph or _HOST.get("x") is not w.x:
+        _HOST.clear()
+        hx, is_bf16 = host_x(w.x)
+        _HOST.update(graph=w.graph, x=w.x, data=(w.graph.indptr.cpu().numpy(), w.graph.indices.cpu().numpy(), hx, is_bf16))
+    return _HOST["data"]
+
+
+def _sampled_parity(fsa, orc, w, B, n_sample, what):
+    """A batch too large for the oracle to redo whole (the benchmark's saturating batch): the GPU
+    runs all B seeds, the oracle a sample of them as a batch of its own -- a seed's IDs and means
+    do not depend on the batch it is in -- and the sampled rows are compared as everywhere else."""
+    from paper_2511_13645_amd import synth
+    fan = list(w.fanouts)
+    g, x = w.graph, w.x
+    seeds = synth.seed_batches(g.num_nodes, B, 1, seed=5)[0]
+    out, h1, ids1, ids2 = fsa.fsa_sample_mean_fwd(g.indptr, g.indices, x, seeds.cuda(), fan, w.sampler_seed)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(B)
+    pick = np.unique(np.concatenate([rng.integers(0, B, n_sample), np.arange(B - 70, B), np.arange(0, 8)]))
+    h_indptr, h_indices, hx, is_bf16 = _host(w)
+    r_out, r_h1, r_ids1, r_ids2 = orc.sample_mean_fwd(h_indptr, h_indices, hx, seeds.numpy()[pick], fan, w.sampler_seed,
+                                                      bf16=is_bf16)
+    sel = torch.from_numpy(pick).cuda()
+    assert_ids_equal(ids1[sel], r_ids1, what + " ids1 (sample)")
+    two = len(fan) == 2
+    if two:
+        assert_ids_equal(ids2[sel], r_ids2, what + " ids2 (sample)")
+    a_out, a_h1 = forward_scales(x, ids1[sel], ids2[sel] if two else None)
+    tol = TOL[x.dtype]
+    worst = assert_close(to_f64(out[sel]), r_out, a_out, tol, what + " out (sample)")
+    if two:
+        worst = max(worst, assert_close(to_f64(h1[sel]), r_h1, a_h1, tol, what + " out_h1 (sample)"))
+    # properties that hold for every seed of the batch: padding, counts within the fanout, replay bitwise
+    assert bool(((ids1 >= -1) & (ids1 < g.num_nodes)).all())
+    if two:
+        assert bool(((ids2 >= -1) & (ids2 < g.num_nodes)).all()) and bool((ids2[ids1 < 0] == -1).all())
+    rp_out, rp_h1 = fsa.fsa_mean_replay_fwd(x, ids1, ids2)
+    torch.cuda.synchronize()
+    assert torch.equal(rp_out.view(torch.uint8), out.view(torch.uint8)), what + " replay out differs"
+    if two:
+        assert torch.equal(rp_h1.view(torch.uint8), h1.view(torch.uint8)), what + " replay h1 differs"
+    print("[%s] B=%d: %d sampled seeds ids bit-exact, worst relative error %.2e; replay of all %d bitwise"
+          % (what, B, pick.size, worst, B), flush=True)
+
+
 def _forward_parity(fsa, orc, w, seeds, what):
     fan = list(w.fanouts)
     g, x = w.graph, w.x
@@ -37,8 +87,7 @@ def _forward_parity(fsa, orc, w, seeds, what):
     out, h1, ids1, ids2 = fsa.fsa_sample_mean_fwd(g.indptr, g.indices, x, d_seeds, fan, w.sampler_seed)
     torch.cuda.synchronize()
     t0 = time.time()
-    h_indptr, h_indices = g.indptr.cpu().numpy(), g.indices.cpu().numpy()
-    hx, is_bf16 = host_x(x)
+    h_indptr, h_indices, hx, is_bf16 = _host(w)
     t1 = time.time()
     r_out, r_h1, r_ids1, r_ids2 = orc.sample_mean_fwd(h_indptr, h_indices, hx, seeds.numpy(), fan, w.sampler_seed,
                                                       bf16=is_bf16)
@@ -107,6 +156,7 @@ def test_kg_shape_one_hop_training(fsa, orc):
     seeds[0] = hub                                           # make sure the longest row is sampled
     ids1, ids2, r_ids1, r_ids2 = _forward_parity(fsa, orc, w, seeds, "kg")
     _backward_parity(fsa, orc, w, ids1, None, r_ids1, None, "kg", with_h1=False)
+    _sampled_parity(fsa, orc, w, 65536 + 37, 800, "kg (several seeds per wave)")
 
 
 def test_citation_shape_two_hop_forward_bf16_wide_indptr(fsa, orc):
@@ -116,6 +166,7 @@ def test_citation_shape_two_hop_forward_bf16_wide_indptr(fsa, orc):
     assert w.graph.num_edges > 2**31 - 1 or abs(w.graph.num_edges / 1.6e9 - 1) < 0.05
     assert w.x.dtype == torch.bfloat16
     _forward_parity(fsa, orc, w, seeds, "citation")
+    _sampled_parity(fsa, orc, w, 65536, 600, "citation (the benchmark's saturating batch)")
 
 
 def test_row_offsets_beyond_32_bits(fsa, orc):
